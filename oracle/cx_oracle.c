@@ -1,0 +1,322 @@
+/*
+ * CPU oracle for the segment-wise gossip parameter-mixing step of Crossover-SGD.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, single-threaded, scalar C, written from the
+ * paper's Algorithm 1 (overlapped segment-wise communication), Algorithm 2
+ * (random topology with fair peer selection) and Section 3.3 (hierarchical
+ * variant).  It shares no code, header, table or constant generator with the
+ * HIP library; only tests, the smoke check and the benchmark's cpu_baseline leg
+ * may call it.  The product path never does.
+ *
+ * Conventions (all matrices row-major, row i = worker i's flat parameter vector):
+ *   x        float [W][ld], columns [0,P) used, [P,ld) never touched
+ *   seg_off  int64 [S+1], non-decreasing, seg_off[0]=0, seg_off[S]=P;
+ *            segment s = columns [seg_off[s], seg_off[s+1])
+ *   peers    int32 [S][n]; peers[s][i] = the row whose segment s row i RECEIVES
+ *            (Algorithm 1: receive_from = destinations[my_rank])
+ * Every function reads only its inputs' round-start values ("snapshot"): in
+ * Algorithm 1 all sends are posted before any averaging happens.
+ * Output buffers must not overlap input buffers.
+ *
+ * Pins (tests/test_oracle_*.py): SplitMix64 published vectors for the bit mixer;
+ * exact draw-tree probabilities for n<=6 (3/8 : 5/8 at n=3); derangement and
+ * double-stochasticity on every table; W=2 / W=3 hand cases; column-mean
+ * conservation; the halving of the deviation norm at W=3; G=W equals the plain
+ * column mean; log2(W) exponential hops equal the exact mean; the fused update
+ * with mixing off equals torch.optim.SGD.  No function here is "parity unpinned".
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------- */
+/* Counter-based random draws (the paper only says "seed = rseed, shared by   */
+/* every process"; a generator keyed by (seed, round, segment, draw index)    */
+/* gives every process the same table and every segment a different one,      */
+/* which Section 3 requires).  The bit mixer is the SplitMix64 output function.*/
+/* ------------------------------------------------------------------------- */
+uint64_t oracle_mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* key of one (round, segment) topology */
+uint64_t oracle_key(uint64_t seed, int32_t round, int32_t segment)
+{
+    uint64_t h = oracle_mix64(seed + 0x9E3779B97F4A7C15ULL);
+    h = oracle_mix64(h + (uint64_t)(uint32_t)round);
+    h = oracle_mix64(h + (uint64_t)(uint32_t)segment);
+    return h;
+}
+
+/* k-th raw 64-bit draw of that topology */
+uint64_t oracle_draw(uint64_t key, uint32_t k)
+{
+    return oracle_mix64(key + (uint64_t)k);
+}
+
+/* uniform integer in [0,m): floor(v * m / 2^64) */
+uint32_t oracle_uniform(uint64_t v, uint32_t m)
+{
+    return (uint32_t)(((unsigned __int128)v * (unsigned __int128)m) >> 64);
+}
+
+/*
+ * Algorithm 2 for one (round, segment): sequential roulette draw.
+ * Row i of the roulette starts uniform over all ranks but i (zero diagonal);
+ * ranks already chosen are zeroed and the row renormalised, so the draw is
+ * uniform over the remaining ranks other than i, taken in ascending rank order.
+ * If the last rank finds only itself left (the printed algorithm would divide
+ * by zero), it swaps with a uniformly drawn earlier rank k: d[n-1]=d[k],
+ * d[k]=n-1, using draw index n.
+ * Returns 0, or -1 if n < 2.
+ */
+int oracle_fair_draw(uint64_t key, int32_t n, int32_t *d)
+{
+    if (n < 2) return -1;
+    unsigned char *taken = (unsigned char *)calloc((size_t)n, 1);
+    if (!taken) return -2;
+    for (int32_t i = 0; i < n; ++i) {
+        uint32_t m = 0;                       /* ranks with non-zero roulette */
+        for (int32_t j = 0; j < n; ++j)
+            if (j != i && !taken[j]) ++m;
+        if (m == 0) {                         /* dead end: only i itself is left */
+            uint32_t k = oracle_uniform(oracle_draw(key, (uint32_t)n), (uint32_t)(n - 1));
+            d[i] = d[k];
+            d[k] = i;
+            taken[i] = 1;
+            continue;
+        }
+        uint32_t t = oracle_uniform(oracle_draw(key, (uint32_t)i), m);
+        for (int32_t j = 0; j < n; ++j) {
+            if (j == i || taken[j]) continue;
+            if (t == 0) { d[i] = j; taken[j] = 1; break; }
+            --t;
+        }
+    }
+    free(taken);
+    return 0;
+}
+
+/*
+ * Peer tables for rounds [round0, round0+R), S segments, n gossiping rows.
+ * mode 0: fair random topology (Algorithm 2), a fresh one per (round, segment).
+ * mode 1: time-varying directed exponential graph (the SGP comparison):
+ *         in round t every row i receives from (i - 2^(t mod ceil(log2 n))) mod n,
+ *         the same shift for every segment.
+ * out: int32 [R][S][n].
+ */
+int oracle_topology(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t R,
+                    int32_t mode, int32_t *out)
+{
+    if (n < 2 || S < 1 || R < 0 || round0 < 0) return -1;
+    int32_t nlog = 0;
+    while (((int64_t)1 << nlog) < (int64_t)n) ++nlog;     /* ceil(log2 n) */
+    for (int32_t r = 0; r < R; ++r) {
+        for (int32_t s = 0; s < S; ++s) {
+            int32_t *d = out + ((int64_t)r * S + s) * n;
+            if (mode == 0) {
+                int rc = oracle_fair_draw(oracle_key(seed, round0 + r, s), n, d);
+                if (rc) return rc;
+            } else if (mode == 1) {
+                int64_t hop = (int64_t)1 << ((round0 + r) % nlog);
+                for (int32_t i = 0; i < n; ++i)
+                    d[i] = (int32_t)((((int64_t)i - hop) % n + n) % n);
+            } else {
+                return -1;
+            }
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Algorithm 1, averaging line: layer = (layer + received_layer) / 2, fp32.  */
+/* ------------------------------------------------------------------------- */
+int oracle_gossip_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P,
+                      int32_t S, const int64_t *seg_off, const int32_t *peers)
+{
+    (void)P;
+    for (int32_t s = 0; s < S; ++s)
+        for (int32_t i = 0; i < W; ++i) {
+            int32_t j = peers[(int64_t)s * W + i];       /* receive_from */
+            for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c)
+                x_out[i * ld + c] = (x_in[i * ld + c] + x_in[j * ld + c]) * 0.5f;
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Hierarchical variant (Section 3.3): (1) reduce inside each group of G      */
+/* consecutive rows to the group mean held by the leader, (2) the L = W/G     */
+/* leaders gossip segment-wise, (3) the leader's result is broadcast to its   */
+/* group.  With L == 1 step (2) is empty and every row gets the global mean.  */
+/* Reference mode: all arithmetic in double, result returned as double.       */
+/* ------------------------------------------------------------------------- */
+int oracle_hier_mix_f64(const float *x_in, double *y_out, int64_t ld, int32_t W, int64_t P,
+                        int32_t G, int32_t S, const int64_t *seg_off,
+                        const int32_t *leader_peers)
+{
+    (void)P;
+    int32_t L = W / G;
+    double *m = (double *)malloc(sizeof(double) * (size_t)L);
+    if (!m) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t g = 0; g < L; ++g) {
+                double acc = 0.0;
+                for (int32_t j = 0; j < G; ++j)
+                    acc += (double)x_in[((int64_t)g * G + j) * ld + c];
+                m[g] = acc / (double)G;
+            }
+            for (int32_t g = 0; g < L; ++g) {
+                double y = m[g];
+                if (L > 1) y = (m[g] + m[leader_peers[(int64_t)s * L + g]]) * 0.5;
+                for (int32_t j = 0; j < G; ++j)
+                    y_out[((int64_t)g * G + j) * ld + c] = y;
+            }
+        }
+    free(m);
+    return 0;
+}
+
+/* fp32 pairwise sum of n values spaced `stride` apart: split at the largest
+ * power of two below n, sum each part the same way, add the two parts. */
+static float tree_sum_f32(const float *x, int64_t stride, int32_t n)
+{
+    if (n == 1) return x[0];
+    int32_t h = 1;
+    while (h * 2 < n) h *= 2;
+    float a = tree_sum_f32(x, stride, h);
+    float b = tree_sum_f32(x + (int64_t)h * stride, stride, n - h);
+    return a + b;
+}
+
+/* Same steps in fp32 with a fixed order: pairwise-tree group sum, times the
+ * fp32 reciprocal of G, then the fp32 pairwise average between leaders. */
+int oracle_hier_mix_f32(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P,
+                        int32_t G, int32_t S, const int64_t *seg_off,
+                        const int32_t *leader_peers)
+{
+    (void)P;
+    int32_t L = W / G;
+    float inv_g = 1.0f / (float)G;
+    float *m = (float *)malloc(sizeof(float) * (size_t)L);
+    if (!m) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t g = 0; g < L; ++g)
+                m[g] = tree_sum_f32(x_in + (int64_t)g * G * ld + c, ld, G) * inv_g;
+            for (int32_t g = 0; g < L; ++g) {
+                float y = m[g];
+                if (L > 1) y = (m[g] + m[leader_peers[(int64_t)s * L + g]]) * 0.5f;
+                for (int32_t j = 0; j < G; ++j)
+                    x_out[((int64_t)g * G + j) * ld + c] = y;
+            }
+        }
+    free(m);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Local momentum-SGD step, then Algorithm 1's averaging on the updated       */
+/* parameters (Section 3.1: averaging happens after the gradient is applied): */
+/*     g' = g + wd*x ;  v' = mu*v + g' ;  x_half = x - lr*v'                  */
+/*     x'_i = (x_half_i + x_half_peer) / 2                                    */
+/* lr, mu, wd are the fp32 hyper-parameter values.  Reference mode: double.   */
+/* ------------------------------------------------------------------------- */
+int oracle_sgd_fused_mix_f64(const float *x_in, const float *v_in, const float *g,
+                             double *x_out, double *v_out, float lr, float mu, float wd,
+                             int64_t ld, int32_t W, int64_t P, int32_t S,
+                             const int64_t *seg_off, const int32_t *peers)
+{
+    (void)P;
+    double *xh = (double *)malloc(sizeof(double) * (size_t)W);
+    if (!xh) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t i = 0; i < W; ++i) {
+                int64_t e = i * ld + c;
+                double gp = (double)g[e] + (double)wd * (double)x_in[e];
+                double vn = (double)mu * (double)v_in[e] + gp;
+                v_out[e] = vn;
+                xh[i] = (double)x_in[e] - (double)lr * vn;
+            }
+            for (int32_t i = 0; i < W; ++i)
+                x_out[i * ld + c] = (xh[i] + xh[peers[(int64_t)s * W + i]]) * 0.5;
+        }
+    free(xh);
+    return 0;
+}
+
+/* Same steps, every operation rounded to fp32, no fused multiply-add
+ * (build with -ffp-contract=off). */
+int oracle_sgd_fused_mix_f32(const float *x_in, const float *v_in, const float *g,
+                             float *x_out, float *v_out, float lr, float mu, float wd,
+                             int64_t ld, int32_t W, int64_t P, int32_t S,
+                             const int64_t *seg_off, const int32_t *peers)
+{
+    (void)P;
+    float *xh = (float *)malloc(sizeof(float) * (size_t)W);
+    if (!xh) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t i = 0; i < W; ++i) {
+                int64_t e = i * ld + c;
+                float t0 = wd * x_in[e];
+                float gp = g[e] + t0;
+                float t1 = mu * v_in[e];
+                float vn = t1 + gp;
+                float t2 = lr * vn;
+                v_out[e] = vn;
+                xh[i] = x_in[e] - t2;
+            }
+            for (int32_t i = 0; i < W; ++i)
+                x_out[i * ld + c] = (xh[i] + xh[peers[(int64_t)s * W + i]]) * 0.5f;
+        }
+    free(xh);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* SGP-style push-sum comparison: every row keeps half of its (x, w) and      */
+/* pushes half to row (i + hop) mod W, i.e. row i receives from (i - hop):    */
+/*     x'_i = (x_i + x_{i-hop}) / 2 ;  w'_i = (w_i + w_{i-hop}) / 2 ;         */
+/*     z_i = x'_i / w'_i  (de-biased parameters, optional).                   */
+/* Whole vector at once (model-wise, S = 1).                                  */
+/* ------------------------------------------------------------------------- */
+int oracle_pushsum_mix_f64(const float *x_in, const float *w_in, double *x_out,
+                           double *w_out, double *z_out /* may be NULL */,
+                           int64_t ld, int32_t W, int64_t P, int32_t hop)
+{
+    for (int32_t i = 0; i < W; ++i) {
+        int32_t j = ((i - hop) % W + W) % W;
+        double wn = ((double)w_in[i] + (double)w_in[j]) * 0.5;
+        w_out[i] = wn;
+        for (int64_t c = 0; c < P; ++c) {
+            double xn = ((double)x_in[i * ld + c] + (double)x_in[j * ld + c]) * 0.5;
+            x_out[i * ld + c] = xn;
+            if (z_out) z_out[i * ld + c] = xn / wn;
+        }
+    }
+    return 0;
+}
+
+int oracle_pushsum_mix_f32(const float *x_in, const float *w_in, float *x_out,
+                           float *w_out, float *z_out /* may be NULL */,
+                           int64_t ld, int32_t W, int64_t P, int32_t hop)
+{
+    for (int32_t i = 0; i < W; ++i) {
+        int32_t j = ((i - hop) % W + W) % W;
+        float wn = (w_in[i] + w_in[j]) * 0.5f;
+        w_out[i] = wn;
+        for (int64_t c = 0; c < P; ++c) {
+            float xn = (x_in[i * ld + c] + x_in[j * ld + c]) * 0.5f;
+            x_out[i * ld + c] = xn;
+            if (z_out) z_out[i * ld + c] = xn / wn;
+        }
+    }
+    return 0;
+}

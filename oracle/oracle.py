@@ -1,0 +1,199 @@
+"""ctypes front end of the plain-C CPU oracle (oracle/cx_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the benchmark's
+cpu_baseline leg.  It imports nothing from the HIP package.  All functions take
+and return NumPy arrays; outputs are fresh arrays (inputs are never modified).
+Matrices are float32 [W][ld] with columns [0,P) in use; `peers[s][i]` is the row
+that row i receives segment s from (Algorithm 1 of the paper).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cx_oracle.c")
+_LIB = os.path.join(_HERE, "libcx_oracle.so")
+_lib = None
+
+__all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topology",
+           "gossip_mix", "hier_mix_f64", "hier_mix_f32", "sgd_fused_mix_f64",
+           "sgd_fused_mix_f32", "pushsum_mix_f64", "pushsum_mix_f32"]
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the oracle with gcc (no FMA contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
+                               "-fexcess-precision=standard", "-Wall", "-Wextra", "-shared",
+                               "-fPIC", "-o", _LIB, _SRC])
+    return _LIB
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build_oracle())
+        u64, i32, i64, f32 = ctypes.c_uint64, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+        vp = ctypes.c_void_p
+        lib.oracle_mix64.restype = u64
+        lib.oracle_mix64.argtypes = [u64]
+        lib.oracle_key.restype = u64
+        lib.oracle_key.argtypes = [u64, i32, i32]
+        lib.oracle_draw.restype = u64
+        lib.oracle_draw.argtypes = [u64, ctypes.c_uint32]
+        lib.oracle_uniform.restype = ctypes.c_uint32
+        lib.oracle_uniform.argtypes = [u64, ctypes.c_uint32]
+        lib.oracle_fair_draw.argtypes = [u64, i32, vp]
+        lib.oracle_topology.argtypes = [u64, i32, i32, i32, i32, i32, vp]
+        lib.oracle_gossip_mix.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp]
+        lib.oracle_hier_mix_f64.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp]
+        lib.oracle_hier_mix_f32.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp]
+        lib.oracle_sgd_fused_mix_f64.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32,
+                                                 i64, i32, i64, i32, vp, vp]
+        lib.oracle_sgd_fused_mix_f32.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32,
+                                                 i64, i32, i64, i32, vp, vp]
+        lib.oracle_pushsum_mix_f64.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
+        lib.oracle_pushsum_mix_f32.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
+        _lib = lib
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+
+
+def _mat(x, dtype=np.float32):
+    x = np.ascontiguousarray(x, dtype=dtype)
+    if x.ndim != 2:
+        raise ValueError("expected a [W][ld] matrix")
+    return x
+
+
+def _seg(seg_off, P):
+    so = np.ascontiguousarray(seg_off, dtype=np.int64)
+    if so.ndim != 1 or len(so) < 2 or so[0] != 0 or so[-1] != P or np.any(np.diff(so) < 0):
+        raise ValueError("seg_off must run non-decreasing from 0 to P")
+    return so
+
+
+def _peers(peers, S, n):
+    p = np.ascontiguousarray(peers, dtype=np.int32).reshape(S, n)
+    if p.min() < 0 or p.max() >= n:
+        raise ValueError("peer index out of range")
+    return p
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"{what} failed with code {rc}")
+
+
+# ------------------------------------------------------------------ topology
+def mix64(z: int) -> int:
+    return int(_L().oracle_mix64(z & (2**64 - 1)))
+
+
+def key(seed: int, rnd: int, seg: int) -> int:
+    return int(_L().oracle_key(seed & (2**64 - 1), rnd, seg))
+
+
+def draw(k: int, idx: int) -> int:
+    return int(_L().oracle_draw(k, idx))
+
+
+def uniform(v: int, m: int) -> int:
+    return int(_L().oracle_uniform(v, m))
+
+
+def fair_draw(k: int, n: int) -> np.ndarray:
+    d = np.full(n, -1, dtype=np.int32)
+    _check(_L().oracle_fair_draw(k, n, _p(d)), "oracle_fair_draw")
+    return d
+
+
+def topology(seed: int, n: int, S: int, round0: int, R: int, mode: int = 0) -> np.ndarray:
+    """int32 [R][S][n] peer tables (mode 0: fair random, 1: directed exponential)."""
+    out = np.full((R, S, n), -1, dtype=np.int32)
+    _check(_L().oracle_topology(seed & (2**64 - 1), n, S, round0, R, mode, _p(out)),
+           "oracle_topology")
+    return out
+
+
+# ----------------------------------------------------------------------- mix
+def gossip_mix(x, P, seg_off, peers) -> np.ndarray:
+    x = _mat(x)
+    W, ld = x.shape
+    so = _seg(seg_off, P)
+    S = len(so) - 1
+    pe = _peers(peers, S, W)
+    out = x.copy()
+    _check(_L().oracle_gossip_mix(_p(x), _p(out), ld, W, P, S, _p(so), _p(pe)), "gossip_mix")
+    return out
+
+
+def _hier(fn, odtype, x, P, G, seg_off, leader_peers):
+    x = _mat(x)
+    W, ld = x.shape
+    if G < 1 or W % G:
+        raise ValueError("G must divide W")
+    L = W // G
+    so = _seg(seg_off, P)
+    S = len(so) - 1
+    pe = _peers(leader_peers, S, L) if L > 1 else None
+    out = x.astype(odtype)
+    _check(fn(_p(x), _p(out), ld, W, P, G, S, _p(so), _p(pe)), "hier_mix")
+    return out
+
+
+def hier_mix_f64(x, P, G, seg_off, leader_peers) -> np.ndarray:
+    return _hier(_L().oracle_hier_mix_f64, np.float64, x, P, G, seg_off, leader_peers)
+
+
+def hier_mix_f32(x, P, G, seg_off, leader_peers) -> np.ndarray:
+    return _hier(_L().oracle_hier_mix_f32, np.float32, x, P, G, seg_off, leader_peers)
+
+
+def _fused(fn, odtype, x, v, g, lr, mu, wd, P, seg_off, peers):
+    x, v, g = _mat(x), _mat(v), _mat(g)
+    if not (x.shape == v.shape == g.shape):
+        raise ValueError("x, v, g must have one shape")
+    W, ld = x.shape
+    so = _seg(seg_off, P)
+    S = len(so) - 1
+    pe = _peers(peers, S, W)
+    xo, vo = x.astype(odtype), v.astype(odtype)
+    _check(fn(_p(x), _p(v), _p(g), _p(xo), _p(vo), lr, mu, wd, ld, W, P, S, _p(so), _p(pe)),
+           "sgd_fused_mix")
+    return xo, vo
+
+
+def sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, seg_off, peers):
+    return _fused(_L().oracle_sgd_fused_mix_f64, np.float64, x, v, g, lr, mu, wd, P, seg_off, peers)
+
+
+def sgd_fused_mix_f32(x, v, g, lr, mu, wd, P, seg_off, peers):
+    return _fused(_L().oracle_sgd_fused_mix_f32, np.float32, x, v, g, lr, mu, wd, P, seg_off, peers)
+
+
+def _push(fn, odtype, x, w, P, hop, want_z):
+    x = _mat(x)
+    W, ld = x.shape
+    w = np.ascontiguousarray(w, dtype=np.float32).reshape(W)
+    if not 1 <= hop < W:
+        raise ValueError("hop must be in [1, W)")
+    xo, wo = x.astype(odtype), w.astype(odtype)
+    zo = x.astype(odtype) if want_z else None
+    _check(fn(_p(x), _p(w), _p(xo), _p(wo), _p(zo), ld, W, P, hop), "pushsum_mix")
+    return xo, wo, zo
+
+
+def pushsum_mix_f64(x, w, P, hop, want_z=True):
+    return _push(_L().oracle_pushsum_mix_f64, np.float64, x, w, P, hop, want_z)
+
+
+def pushsum_mix_f32(x, w, P, hop, want_z=True):
+    return _push(_L().oracle_pushsum_mix_f32, np.float32, x, w, P, hop, want_z)

@@ -1,0 +1,296 @@
+"""Pins for the oracle's mixing functions: hand cases, closed forms, invariants and
+library special cases.  CPU only; nothing here calls the HIP library."""
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2012_15198_amd import workloads as WL
+
+F = np.float32
+
+
+def f32(a):
+    return np.asarray(a, dtype=np.float32)
+
+
+# ----------------------------------------------------------------- Algorithm 1
+def test_w2_pair_becomes_its_average_and_stays():
+    x = f32([[1.0, -3.5, 1e-3, 16777217.0], [2.0, 0.25, 7.0, 1.0]])
+    so = [0, 4]
+    y = O.gossip_mix(x, 4, so, [[1, 0]])
+    want = (x[0] + x[1]) * F(0.5)
+    assert (y[0] == want).all() and (y[1] == want).all()
+    assert (O.gossip_mix(y, 4, so, [[1, 0]]) == y).all()
+
+
+def test_w3_hand_case_pins_the_direction_of_the_table():
+    # peers[i] is who i RECEIVES from: out_i = (x_i + x_peers[i]) / 2
+    x = f32([[1, 2], [3, 5], [7, 11]])
+    y = O.gossip_mix(x, 2, [0, 2], [[1, 2, 0]])
+    assert y.tolist() == [[2.0, 3.5], [5.0, 8.0], [4.0, 6.5]]
+    # the inverse table gives a different (wrong-direction) answer
+    y2 = O.gossip_mix(x, 2, [0, 2], [[2, 0, 1]])
+    assert y2.tolist() == [[4.0, 6.5], [2.0, 3.5], [5.0, 8.0]]
+
+
+def test_each_segment_uses_its_own_table_and_old_values():
+    x = f32([[1, 10, 100], [2, 20, 200], [4, 40, 400]])
+    # segment 0 = column 0 with cycle 0<-1<-2<-0, segment 1 = columns 1..2 reversed cycle
+    y = O.gossip_mix(x, 3, [0, 1, 3], [[1, 2, 0], [2, 0, 1]])
+    assert y.tolist() == [[1.5, 25.0, 250.0], [3.0, 15.0, 150.0], [2.5, 30.0, 300.0]]
+
+
+def test_padding_is_untouched_and_result_independent_of_ld():
+    wl = dict(W=5, P=37, sigma=1.0, seed=3)
+    a = WL.gen_matrix(ld=37, **wl)
+    b = WL.gen_matrix(ld=48, **wl)
+    assert (a == b[:, :37]).all()
+    so = WL.equal_seg_off(37, 3)
+    pe = O.topology(1, 5, 3, 0, 1)[0]
+    ya, yb = O.gossip_mix(a, 37, so, pe), O.gossip_mix(b, 37, so, pe)
+    assert (ya == yb[:, :37]).all()
+    assert (yb[:, 37:] == b[:, 37:]).all()
+
+
+def test_empty_segments_are_allowed():
+    x = WL.gen_matrix(4, 10, 1.0, 1)
+    pe = O.topology(1, 4, 3, 0, 1)[0]
+    y = O.gossip_mix(x, 10, [0, 0, 10, 10], pe)
+    assert (y == O.gossip_mix(x, 10, [0, 10], pe[1:2])).all()
+
+
+def test_same_table_on_all_segments_equals_model_wise():
+    x = WL.gen_matrix(6, 50, 1.0, 2)
+    d = O.topology(9, 6, 1, 0, 1)[0, 0]
+    y1 = O.gossip_mix(x, 50, [0, 50], [d])
+    y4 = O.gossip_mix(x, 50, WL.equal_seg_off(50, 4), [d] * 4)
+    assert (y1 == y4).all()
+
+
+def test_column_mean_is_preserved_and_spread_shrinks():
+    W, P, S, R = 8, 400, 4, 12
+    x = WL.gen_matrix(W, P, 1.0, 5)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(5, W, S, 0, R)
+    mean0 = x.astype(np.float64).mean(0)
+    prev_var = x.astype(np.float64).var(0)
+    for r in range(R):
+        x = O.gossip_mix(x, P, so, tabs[r])
+        x64 = x.astype(np.float64)
+        assert np.abs(x64.mean(0) - mean0).max() <= (r + 1) * 2.0 ** -24 * 4.0
+        var = x64.var(0)
+        assert (var <= prev_var * (1 + 1e-6) + 1e-12).all()
+        prev_var = var
+
+
+def test_many_rounds_converge_to_the_column_mean():
+    W, P = 8, 64
+    x = WL.gen_matrix(W, P, 1.0, 6)
+    mean0 = x.astype(np.float64).mean(0)
+    tabs = O.topology(6, W, 2, 0, 80)
+    for r in range(80):
+        x = O.gossip_mix(x, P, [0, 32, 64], tabs[r])
+    assert np.abs(x - mean0).max() < 1e-5
+
+
+def test_identical_rows_are_a_bit_exact_fixed_point():
+    row = WL.edge_values(97, 1)
+    row = row[np.isfinite(row) & (np.abs(row) < 1e38)]
+    x = np.tile(row, (6, 1))
+    y = O.gossip_mix(x, x.shape[1], [0, x.shape[1]], O.topology(2, 6, 1, 0, 1)[0])
+    assert (y.view(np.uint32) == x.view(np.uint32)).all()
+
+
+def test_w3_deviation_norm_halves_every_round():
+    # (I+C)/2 and (I+C^2)/2 are circulants whose non-unit eigenvalues have modulus 1/2
+    x = WL.gen_matrix(3, 200, 1.0, 7)
+    tabs = O.topology(7, 3, 1, 0, 6)
+    dev = lambda a: np.linalg.norm(a.astype(np.float64) - a.astype(np.float64).mean(0), axis=0)
+    d0 = dev(x)
+    for r in range(6):
+        x = O.gossip_mix(x, 200, [0, 200], tabs[r])
+        d1 = dev(x)
+        assert np.allclose(d1, d0 / 2, rtol=2e-5, atol=1e-7)
+        d0 = d1
+
+
+def test_matches_dense_mixing_matrix_product():
+    W, P = 7, 30
+    x = WL.gen_matrix(W, P, 1.0, 8)
+    so = WL.equal_seg_off(P, 3)
+    pe = O.topology(8, W, 3, 0, 1)[0]
+    y = O.gossip_mix(x, P, so, pe)
+    for s in range(3):
+        M = 0.5 * np.eye(W)
+        M[np.arange(W), pe[s]] += 0.5
+        ref = M @ x[:, so[s]:so[s + 1]].astype(np.float64)
+        assert np.abs(y[:, so[s]:so[s + 1]] - ref).max() < 1e-6
+
+
+# --------------------------------------------------------------- hierarchical
+def test_hier_g1_is_plain_gossip():
+    W, P = 6, 45
+    x = WL.gen_matrix(W, P, 1.0, 9)
+    so = WL.equal_seg_off(P, 3)
+    pe = O.topology(9, W, 3, 0, 1)[0]
+    g = O.gossip_mix(x, P, so, pe)
+    assert (O.hier_mix_f32(x, P, 1, so, pe) == g).all()
+    assert np.abs(O.hier_mix_f64(x, P, 1, so, pe) - g).max() < 1e-6
+
+
+def test_hier_one_group_is_the_allreduce_mean():
+    W, P = 8, 33
+    x = WL.gen_matrix(W, P, 1.0, 10)
+    ref = np.tile(x.astype(np.float64).mean(0), (W, 1))
+    assert np.abs(O.hier_mix_f64(x, P, W, [0, P], None) - ref).max() < 1e-15
+    assert np.abs(O.hier_mix_f32(x, P, W, [0, P], None) - ref).max() < 1e-6
+
+
+def test_hier_hand_case():
+    # W=4, G=2 -> leaders 0 and 2 swap; every row ends at the global mean
+    x = f32([[1, 8], [3, 0], [5, 2], [7, 6]])
+    y = O.hier_mix_f64(x, 2, 2, [0, 2], [[1, 0]])
+    assert y.tolist() == [[4.0, 4.0]] * 4
+    # W=6, G=2, 3 leaders with table [1,2,0]: means (2,4),(6,4),(10,0)
+    x = f32([[1, 8], [3, 0], [5, 2], [7, 6], [9, -1], [11, 1]])
+    y = O.hier_mix_f64(x, 2, 2, [0, 2], [[1, 2, 0]])
+    assert y.tolist() == [[4, 4], [4, 4], [8, 2], [8, 2], [6, 2], [6, 2]]
+    assert O.hier_mix_f32(x, 2, 2, [0, 2], [[1, 2, 0]]).tolist() == y.tolist()
+
+
+def test_hier_members_identical_mean_preserved_then_noop():
+    W, P, G, S = 16, 120, 4, 3
+    x = WL.gen_matrix(W, P, 1.0, 11)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(11, W // G, S, 0, 2)
+    y = O.hier_mix_f32(x, P, G, so, tabs[0])
+    assert (y.reshape(W // G, G, P) == y.reshape(W // G, G, P)[:, :1]).all()
+    assert np.abs(y.astype(np.float64).mean(0) - x.astype(np.float64).mean(0)).max() < 1e-6
+    # second round: the group mean of identical rows is exact for a power-of-two G,
+    # so it equals plain gossip between the leaders, bit for bit
+    y2 = O.hier_mix_f32(y, P, G, so, tabs[1])
+    lead = O.gossip_mix(y[::G], P, so, tabs[1])
+    assert (y2[::G] == lead).all()
+    assert np.abs(O.hier_mix_f64(x, P, G, so, tabs[0]) - y).max() < 1e-6
+
+
+def test_f32_group_sum_is_the_pairwise_tree():
+    # (1e8 + 1) rounds to 1e8: tree = (1e8+1) + (-1e8+1) = 0, a running sum gives 1
+    x = f32([[1e8], [1.0], [-1e8], [1.0]])
+    assert O.hier_mix_f32(x, 1, 4, [0, 1], None)[0, 0] == 0.0
+    # G=3 splits 2+1: (1 + 1e8) + (-1e8) = 0, whereas 1 + (1e8 - 1e8) = 1
+    x = f32([[1.0], [1e8], [-1e8]])
+    assert O.hier_mix_f32(x, 1, 3, [0, 1], None)[0, 0] == 0.0
+    # G=5 splits 4+1 and G=6 splits 4+2: compare with the same tree built by hand
+    v = WL.gen_matrix(6, 1, 1.0, 12)[:, 0]
+    t4 = (v[0] + v[1]) + (v[2] + v[3])
+    assert O.hier_mix_f32(v[:5, None], 1, 5, [0, 1], None)[0, 0] == (t4 + v[4]) * (F(1) / F(5))
+    assert O.hier_mix_f32(v[:, None], 1, 6, [0, 1], None)[0, 0] == (t4 + (v[4] + v[5])) * (F(1) / F(6))
+
+
+# ------------------------------------------------------------------ fused SGD
+def test_fused_hand_case_plain_sgd_then_average():
+    # mu = 0, wd = 0: x_half = x - lr*g, then pairwise average
+    x = f32([[1.0, 2.0], [3.0, 4.0]])
+    g = f32([[2.0, -4.0], [6.0, 8.0]])
+    v = np.zeros_like(x)
+    xo, vo = O.sgd_fused_mix_f64(x, v, g, 0.5, 0.0, 0.0, 2, [0, 2], [[1, 0]])
+    # x_half = [[0,4],[0,0]] -> both rows [0,2]; v = g
+    assert xo.tolist() == [[0.0, 2.0], [0.0, 2.0]] and vo.tolist() == g.tolist()
+    x32, v32 = O.sgd_fused_mix_f32(x, v, g, 0.5, 0.0, 0.0, 2, [0, 2], [[1, 0]])
+    assert x32.tolist() == xo.tolist() and v32.tolist() == vo.tolist()
+
+
+def test_fused_momentum_and_weight_decay_by_hand():
+    # one element, identity table (no mixing): g' = g + wd*x = 1 + 0.5*2 = 2,
+    # v' = mu*v + g' = 0.5*4 + 2 = 4, x' = x - lr*v' = 2 - 0.25*4 = 1
+    xo, vo = O.sgd_fused_mix_f64(f32([[2.0]] * 2), f32([[4.0]] * 2), f32([[1.0]] * 2),
+                                 0.25, 0.5, 0.5, 1, [0, 1], [[0, 1]])
+    assert xo.tolist() == [[1.0], [1.0]] and vo.tolist() == [[4.0], [4.0]]
+
+
+def test_fused_without_mixing_equals_library_momentum_sgd():
+    import torch
+    W, P = 3, 40
+    lr, mu, wd = 0.1, 0.9, 1e-4
+    x = WL.gen_matrix(W, P, 0.05, 13)
+    ident = [np.arange(W)]
+    p = torch.nn.Parameter(torch.from_numpy(x.copy()).double())
+    opt = torch.optim.SGD([p], lr=float(F(lr)), momentum=float(F(mu)), weight_decay=float(F(wd)))
+    xo = x.astype(np.float64)
+    vo = np.zeros_like(xo)
+    for step in range(3):
+        g = WL.gen_matrix(W, P, 1e-2, 13, stream=10 + step)
+        p.grad = torch.from_numpy(g.copy()).double()
+        opt.step()
+        # the oracle takes fp32 inputs: feed it the rounded running state and compare one step
+        x_in, v_in = xo.astype(np.float32), vo.astype(np.float32)
+        x1, v1 = O.sgd_fused_mix_f64(x_in, v_in, g, lr, mu, wd, P, [0, P], ident)
+        # one step of the library from the same rounded state
+        q = torch.nn.Parameter(torch.from_numpy(x_in.copy()).double())
+        o2 = torch.optim.SGD([q], lr=float(F(lr)), momentum=float(F(mu)), weight_decay=float(F(wd)))
+        o2.state[q]["momentum_buffer"] = torch.from_numpy(v_in.copy()).double()
+        q.grad = torch.from_numpy(g.copy()).double()
+        o2.step()
+        assert np.abs(x1 - q.detach().numpy()).max() < 1e-15
+        assert np.abs(v1 - o2.state[q]["momentum_buffer"].numpy()).max() < 1e-15
+        xo, vo = x1, v1
+    assert np.abs(xo - p.detach().numpy()).max() < 1e-6
+
+
+def test_fused_lr0_is_plain_gossip_and_f32_tracks_f64():
+    W, P, S = 6, 70, 3
+    x = WL.gen_matrix(W, P, 0.05, 14)
+    v = WL.gen_matrix(W, P, 0.01, 14, stream=1)
+    g = WL.gen_matrix(W, P, 0.01, 14, stream=2)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(14, W, S, 0, 1)[0]
+    x0, _ = O.sgd_fused_mix_f32(x, v, g, 0.0, 0.9, 1e-4, P, so, pe)
+    assert (x0 == O.gossip_mix(x, P, so, pe)).all()
+    xa, va = O.sgd_fused_mix_f32(x, v, g, 0.1, 0.9, 1e-4, P, so, pe)
+    xb, vb = O.sgd_fused_mix_f64(x, v, g, 0.1, 0.9, 1e-4, P, so, pe)
+    assert np.abs(xa - xb).max() < 1e-6 * np.abs(x).max()
+    assert np.abs(va - vb).max() < 1e-6 * max(np.abs(v).max(), np.abs(g).max())
+
+
+# ------------------------------------------------------------------- push-sum
+def test_pushsum_hand_case_and_direction():
+    x = f32([[0.0], [4.0], [8.0], [16.0]])
+    w = f32([1, 1, 1, 1])
+    xo, wo, zo = O.pushsum_mix_f64(x, w, 1, 1)
+    # row i receives from i-1: (0+16)/2, (4+0)/2, (8+4)/2, (16+8)/2
+    assert xo[:, 0].tolist() == [8.0, 2.0, 6.0, 12.0]
+    assert wo.tolist() == [1.0] * 4 and zo[:, 0].tolist() == xo[:, 0].tolist()
+    # unequal weights: w' = (w_i + w_{i-1})/2 and z = x'/w'
+    xo, wo, zo = O.pushsum_mix_f64(x, f32([1, 3, 1, 3]), 1, 1)
+    assert wo.tolist() == [2.0] * 4 and zo[:, 0].tolist() == [4.0, 1.0, 3.0, 6.0]
+
+
+def test_pushsum_equals_gossip_with_the_shift_table_and_keeps_weight():
+    W, P = 8, 50
+    x = WL.gen_matrix(W, P, 1.0, 15)
+    w = np.ones(W, dtype=np.float32)
+    for r in range(5):
+        shift = O.topology(0, W, 1, r, 1, mode=1)[0]
+        hop = int((0 - shift[0, 0]) % W)
+        xo, wo, zo = O.pushsum_mix_f32(x, w, P, hop)
+        assert (xo == O.gossip_mix(x, P, [0, P], shift)).all()
+        assert (wo == 1).all() and (zo == xo).all()
+        x, w = xo, wo
+
+
+@pytest.mark.parametrize("W", [4, 16, 128])
+def test_log2w_exponential_hops_give_the_exact_mean(W):
+    # prod_k (I + C^(2^k))/2 = (1/W) * sum_j C^j for W a power of two
+    P = 20
+    x = WL.gen_matrix(W, P, 1.0, 16)
+    mean = x.astype(np.float64).mean(0)
+    x64, w64 = x.astype(np.float64), np.ones(W)
+    xf, wf = x, np.ones(W, dtype=np.float32)
+    for k in range(int(np.log2(W))):
+        xf, wf, _ = O.pushsum_mix_f32(xf, wf, P, 2 ** k)
+        x64n, w64, _ = O.pushsum_mix_f64(x64.astype(np.float32), w64.astype(np.float32), P, 2 ** k)
+        x64 = x64n
+    assert np.abs(xf - mean).max() < 1e-6
+    assert np.abs(x64 - mean).max() < 1e-6
+    assert abs(wf.sum() - W) == 0
