@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the segment-wise gossip mixing path on one MI355X.
+
+A step is one gossip round over the whole workload: generate the round's peer tables
+(Algorithm 2, host), upload them (a few KB), and run one mixing launch over all W rows
+(Algorithm 1) in place.  The parameter matrix is resident in HBM before timing starts.
+Prints ONE JSON line (see the design doc for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--all]
+                    [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def describe(wl) -> str:
+    s = f"{wl.name}: W={wl.W} P={wl.P} fp32 S={wl.S}"
+    if wl.G > 1:
+        s += f" hierarchical G={wl.G} L={wl.L}"
+    if wl.layers:
+        s += f" segments on {wl.layers} ragged layer boundaries"
+    return s
+
+
+class Runner:
+    """Holds one workload's device state and issues its steps."""
+
+    def __init__(self, wl, kind, total_rounds):
+        import torch
+        from paper_2012_15198_amd import cxmix as cx
+        from paper_2012_15198_amd import workloads as WL
+        self.torch, self.cx, self.wl, self.kind = torch, cx, wl, kind
+        dev = "cuda:0"
+        self.so_host = WL.seg_off_for(wl)
+        cx.cx_check_segments(self.so_host, wl.P)
+        self.so = torch.from_numpy(self.so_host).to(dev)
+        self.x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, device=dev)
+        self.n = wl.L if kind == "hier" else wl.W
+        self.S = 1 if kind == "pushsum" else wl.S
+        self.mode = 1 if kind == "pushsum" else 0
+        # one pinned + one device slot per round, so the host can run ahead of the GPU
+        self.tab_host = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, pin_memory=True)
+        self.tab_np = self.tab_host.numpy()
+        self.tab_dev = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, device=dev)
+        self.bytes_per_elem = 8
+        if kind == "fused":
+            self.v = torch.zeros_like(self.x)
+            self.g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, stream=2, device=dev)
+            self.bytes_per_elem = 20
+        if kind == "pushsum":
+            self.w = [torch.ones(wl.W, device=dev), torch.zeros(wl.W, device=dev)]
+        self.round = 0
+        self.ev = []
+        torch.cuda.synchronize()
+
+    def step(self, timed: bool):
+        torch, cx, wl, r = self.torch, self.cx, self.wl, self.round
+        cx.cx_topology_gen(wl.seed, self.n, self.S, r, 1, self.mode, out=self.tab_np[r:r + 1])
+        self.tab_dev[r].copy_(self.tab_host[r], non_blocking=True)
+        tab = self.tab_dev[r]
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        if self.kind == "gossip":
+            cx.cx_gossip_mix(self.x, self.x, wl.P, self.so, tab)
+        elif self.kind == "hier":
+            cx.cx_hier_mix(self.x, self.x, wl.P, wl.G, self.so, tab)
+        elif self.kind == "fused":
+            cx.cx_sgd_fused_mix(self.x, self.x, self.v, self.v, self.g, wl.lr, wl.mu, wl.wd, wl.P,
+                                self.so, tab)
+        elif self.kind == "pushsum":
+            hop = int((0 - int(self.tab_np[r, 0, 0])) % wl.W)
+            cx.cx_pushsum_mix(self.x, self.x, self.w[r & 1], self.w[1 - (r & 1)], None, wl.P, hop)
+        if timed:
+            e1.record()
+            self.ev.append((e0, e1))
+        self.round += 1
+
+    def run(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step(True)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kernel_ms = [a.elapsed_time(b) for a, b in self.ev]
+        wl = self.wl
+        elems = wl.W * wl.P
+        alg_bytes = elems * self.bytes_per_elem
+        ms_step = wall * 1e3 / steps
+        k_avg = float(np.mean(kernel_ms))
+        return {
+            "kind": self.kind, "ms_per_step": ms_step,
+            "GBps": alg_bytes / (ms_step * 1e-3) / 1e9,
+            "params_mixed_per_s": elems / (ms_step * 1e-3),
+            "kernel_ms_avg": k_avg, "kernel_ms_min": float(np.min(kernel_ms)),
+            "kernel_ms_median": float(np.median(kernel_ms)),
+            "kernel_GBps": alg_bytes / (k_avg * 1e-3) / 1e9,
+            "alg_bytes_per_launch": alg_bytes,
+        }
+
+
+def copy_ceiling(nbytes, reps=10):
+    """Plain streaming copy with the same footprint split (read n/2, write n/2)."""
+    import torch
+    from paper_2012_15198_amd import cxmix as cx
+    n = (nbytes // 8) // 4 * 4
+    src = torch.empty(n, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        cx.cx_copy_baseline(src, dst)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        cx.cx_copy_baseline(src, dst)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    return {"GBps": 8.0 * n / (ms * 1e-3) / 1e9, "ms": ms, "bytes": 8 * n}
+
+
+def cpu_baseline(runner, budget_s=12.0):
+    """The CPU oracle, as it stands, timed on this host: full rounds of the same workload."""
+    import oracle as O
+    wl = runner.wl
+    x = runner.x.cpu().numpy()
+    out = np.empty_like(x)
+    tabs = O.topology(wl.seed, wl.W, wl.S, 0, 64)
+    O.gossip_mix(x, wl.P, runner.so_host, tabs[0], out=out)      # touch the pages
+    rounds, t0 = 0, time.perf_counter()
+    while True:
+        O.gossip_mix(x, wl.P, runner.so_host, tabs[(rounds + 1) % 64], out=out)
+        x, out = out, x
+        rounds += 1
+        dt = time.perf_counter() - t0
+        if dt > budget_s or rounds >= 40:
+            break
+    elems = wl.W * wl.P
+    return {"value": 8.0 * elems * rounds / dt / 1e9, "unit": "GB/s",
+            "params_mixed_per_s": elems * rounds / dt, "s_per_round": dt / rounds,
+            "cores": 1, "kind": "oracle",
+            "sample": f"{rounds} full rounds of {describe(wl)} (oracle_gossip_mix, single thread, "
+                      f"{os.cpu_count()} host cores visible)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--all", action="store_true", help="also time the other workloads' entry points")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-copy", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (W simulated workers share one MI355X); "
+                 "--gpus must be 1")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2012_15198_amd import cxmix as cx
+    from paper_2012_15198_amd import workloads as WL
+    cx.lib()                                            # fail loudly if the library is not built
+
+    wl = WL.WORKLOADS[args.workload]
+    kind = {"gossip": "gossip", "hier": "hier", "fused+pushsum": "fused"}[wl.kind]
+    runner = Runner(wl, kind, args.steps + args.warmup)
+    res = runner.run(args.steps, args.warmup)
+    out = {
+        "metric": "gossip-mix HBM GB/s and params-mixed/s per round (fraction of HBM peak), 1 GPU",
+        "value": res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": describe(wl), "entry_point": f"cx_{kind}_mix" if kind != "fused" else "cx_sgd_fused_mix",
+                   "rounds_timed": args.steps, "in_place": True,
+                   "step": "cx_topology_gen(1 round) + table upload + one mixing launch"},
+        "params_mixed_per_s": res["params_mixed_per_s"],
+        "frac_of_hbm_peak": res["GBps"] / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": res["kernel_GBps"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": res["kernel_GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "mix_kernel", "kernel_ms_avg": res["kernel_ms_avg"],
+                     "kernel_ms_min": res["kernel_ms_min"], "kernel_ms_median": res["kernel_ms_median"],
+                     "alg_bytes_per_launch": res["alg_bytes_per_launch"]},
+    }
+    if not args.no_copy:
+        out["copy_ceiling"] = copy_ceiling(res["alg_bytes_per_launch"])
+    if not args.no_cpu_baseline and kind == "gossip":
+        out["cpu_baseline"] = cpu_baseline(runner)
+    else:
+        out["cpu_baseline"] = None
+    del runner
+    torch.cuda.empty_cache()
+
+    if args.all:
+        others = {}
+        plan = [("C1", "gossip", 50), ("C3", "hier", 20), ("C4", "fused", 10), ("C4", "pushsum", 20),
+                ("C5", "hier", 10)]
+        for name, k, steps in plan:
+            if name == args.workload and k == kind:
+                continue
+            r = Runner(WL.WORKLOADS[name], k, steps + 3)
+            rr = r.run(steps, 3)
+            rr["workload"] = describe(WL.WORKLOADS[name])
+            rr["frac_of_hbm_peak_kernel"] = rr["kernel_GBps"] / HBM_PEAK_GBPS
+            others[f"{name}:{k}"] = rr
+            del r
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,167 @@
+/*
+ * cx_mix.h -- C ABI of the MI355X (gfx950) segment-wise gossip parameter-mixing library.
+ *
+ * The library implements the data-parallel hot path of Crossover-SGD
+ * (arXiv 2012.15198): W simulated workers' flat fp32 parameter vectors are the rows
+ * of one HBM-resident matrix, every vector is cut into S segments, and in every
+ * round each segment of each row is averaged with the same segment of a peer row
+ * taken from a per-(round, segment) peer table (Algorithm 1); the tables come from
+ * the random topology with fair peer selection (Algorithm 2).
+ *
+ * Common conventions
+ *   x          float32 [W][ld] row-major DEVICE memory, row i = worker i; columns
+ *              [0,P) are used, [P,ld) are never read or written.  ld % 4 == 0 and
+ *              16-byte aligned base pointers are required (CX_ERR_ALIGN otherwise).
+ *   seg_off    int64 [S+1] DEVICE memory, non-decreasing, seg_off[0] = 0,
+ *              seg_off[S] = P; segment s = columns [seg_off[s], seg_off[s+1]).
+ *              Segment starts need not be multiples of 4.  Empty segments are fine.
+ *   peers      int32 [S][n] DEVICE memory for ONE round; peers[s][i] is the row
+ *              whose segment s row i RECEIVES and averages with (Algorithm 1:
+ *              receive_from = destinations[my_rank]).  Each peers[s] must be a
+ *              permutation of 0..n-1; the method's tables also have no fixed point.
+ *   stream     a hipStream_t passed as void* (NULL = the default stream).  Mixing
+ *              calls only enqueue work: they never synchronise, never allocate and
+ *              never free device memory.  The caller owns every buffer and must keep
+ *              it alive until the stream has passed the call.
+ *   in place   x_out may be the same pointer as x_in (each element is then read
+ *              once and written once); otherwise the two matrices must not overlap
+ *              (CX_ERR_ALIAS).  All values are computed from the round's input rows
+ *              (Algorithm 1 posts every send before any averaging).
+ *   limits     at most CX_MAX_ROWS gossiping rows (W, or W/G in hierarchical mode).
+ *   return     CX_OK (0) or a negative cx_status.  Argument errors are detected on
+ *              the host before anything is enqueued.  Device tables are NOT read by
+ *              the host: check their host mirrors with cx_check_segments /
+ *              cx_check_peers before uploading.  The kernels never index out of
+ *              bounds on a bad table: segment offsets are clamped to [0,P] and a
+ *              peers[s] that is not a permutation of 0..n-1 is replaced, for that
+ *              segment, by the identity (every row pairs with itself: no mixing).
+ */
+#ifndef CX_MIX_H
+#define CX_MIX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CX_MAX_ROWS 1024
+
+enum cx_status {
+    CX_OK = 0,
+    CX_ERR_NULL = -1,        /* a required pointer is NULL */
+    CX_ERR_SHAPE = -2,       /* W, P, S, G, ld, hop, R ... out of range */
+    CX_ERR_SEGMENTS = -3,    /* seg_off is not 0 = o[0] <= o[1] <= ... <= o[S] = P */
+    CX_ERR_PEERS = -4,       /* a peer row is not a fixed-point-free permutation */
+    CX_ERR_ALIGN = -5,       /* pointer not 16-byte aligned or ld % 4 != 0 */
+    CX_ERR_ALIAS = -6,       /* buffers overlap in an unsupported way */
+    CX_ERR_HIP = -7,         /* the HIP runtime reported an error at launch */
+    CX_ERR_UNSUPPORTED = -8  /* valid request this build cannot serve (see each call) */
+};
+
+/* Human-readable name of a status code (static storage). */
+const char *cx_status_string(int status);
+
+/* ABI version of this header (bumped on any signature change). */
+int cx_abi_version(void);
+
+/* ------------------------------------------------------------------------------------
+ * cx_topology_gen -- Algorithm 2, "random topology with fair peer selection", for
+ * rounds [round0, round0+R), S segments and n gossiping rows.  HOST call, host memory.
+ *   mode 0  fair random topology: for i = 0..n-1 draw uniformly among the rows that are
+ *           neither i (zero diagonal of the roulette) nor already chosen, candidates in
+ *           ascending order.  If the last row finds only itself left, it swaps with a
+ *           uniformly drawn earlier row k (d[n-1] = d[k], d[k] = n-1).  Draws come from
+ *           a counter-based generator keyed by (seed, round, segment, draw index), so a
+ *           table is a pure function of its coordinates: every worker derives the same
+ *           one from the shared seed, every segment gets a different one (Section 3),
+ *           and a run can be resumed at any round.
+ *   mode 1  time-varying directed exponential graph of the SGP comparison: in round t
+ *           row i receives from (i - 2^(t mod ceil(log2 n))) mod n, for every segment.
+ *   peers_host  int32 [R][S][n], caller-allocated, written completely on success.
+ * Errors: CX_ERR_NULL; CX_ERR_SHAPE if n < 2, n > CX_MAX_ROWS, S < 1, R < 0, round0 < 0
+ * or round0 + R overflows; CX_ERR_UNSUPPORTED for an unknown mode.
+ */
+int cx_topology_gen(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t R,
+                    int32_t mode, int32_t *peers_host);
+
+/* Host-side checks of the host mirrors of the device tables (Section 3.2: every row is
+ * chosen exactly once and nobody chooses itself).  peers_host is int32 [S][n]. */
+int cx_check_segments(const int64_t *seg_off_host, int32_t S, int64_t P);
+int cx_check_peers(const int32_t *peers_host, int32_t S, int32_t n);
+
+/* ------------------------------------------------------------------------------------
+ * cx_gossip_mix -- Algorithm 1, averaging step, for all W rows at once:
+ *     x_out[i][c] = (x_in[i][c] + x_in[peers[s][i]][c]) * 0.5f   for c in segment s,
+ * one fp32 add and one fp32 multiply per element (round-to-nearest-even, subnormals
+ * kept), so results are bit-identical to that formula evaluated in any language.
+ * Errors: CX_ERR_NULL; CX_ERR_SHAPE if W < 2, W > CX_MAX_ROWS, S < 1, P < 1, ld < P;
+ * CX_ERR_ALIGN; CX_ERR_ALIAS; CX_ERR_UNSUPPORTED if flags != 0; CX_ERR_HIP.
+ */
+int cx_gossip_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P,
+                  int32_t S, const int64_t *seg_off_dev, const int32_t *peers_dev,
+                  uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * cx_hier_mix -- hierarchical Crossover-SGD (Section 3.3) on parameters: groups are G
+ * consecutive rows, the first row of a group is its leader, L = W / G.
+ *     m_g  = (pairwise-tree fp32 sum of the G rows of group g) * (1.0f / G)
+ *     y_g  = (m_g + m_{leader_peers[s][g]}) * 0.5f          (skipped when L == 1)
+ *     every row of group g  <-  y_g
+ * The tree splits a run of k rows at the largest power of two below k.
+ * leader_peers_dev is int32 [S][L] (may be NULL when L == 1: the result is then the
+ * global mean, i.e. the AllReduce mixing matrix).
+ * Errors: as cx_gossip_mix, plus CX_ERR_SHAPE if G < 1, W % G != 0 or L > CX_MAX_ROWS;
+ * CX_ERR_UNSUPPORTED if G is not one of 1, 2, 4, 8, 16.
+ */
+int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P,
+                int32_t G, int32_t S, const int64_t *seg_off_dev,
+                const int32_t *leader_peers_dev, uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * cx_pushsum_mix -- SGP-style push-sum comparison (Sections 2.1 and 3): every row keeps
+ * half of (x, w) and pushes half to row (i + hop) mod W, model-wise (one segment):
+ *     j = (i - hop) mod W
+ *     x_out[i] = (x_in[i] + x_in[j]) * 0.5f ;  w_out[i] = (w_in[i] + w_in[j]) * 0.5f
+ *     z_out[i] = x_out[i] / w_out[i]            (only if z_out != NULL)
+ * w_in / w_out are float32 [W] DEVICE vectors and must not overlap each other.
+ * z_out (float32 [W][ld]) must not overlap x_in or x_out.
+ * Errors: as cx_gossip_mix, plus CX_ERR_SHAPE if hop is outside [1, W).
+ */
+int cx_pushsum_mix(const float *x_in, float *x_out, const float *w_in, float *w_out,
+                   float *z_out, int64_t ld, int32_t W, int64_t P, int32_t hop,
+                   uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * cx_sgd_fused_mix -- local momentum-SGD step fused in front of Algorithm 1's averaging
+ * (Section 3.1: parameters are averaged after the gradient has been applied):
+ *     t = g + wd * x ;  v' = mu * v + t ;  h = x - lr * v'       (per row, fp32, no FMA)
+ *     x_out[i][c] = (h[i][c] + h[peers[s][i]][c]) * 0.5f ;  v_out = v'
+ * v_out may equal v_in (in place) and x_out may equal x_in; g is only read.
+ * x, v and g share shape and ld.  Each of x, v, g is read once, x and v written once.
+ * Errors: as cx_gossip_mix.
+ */
+int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *v_out,
+                     const float *g, float lr, float mu, float wd, int64_t ld, int32_t W,
+                     int64_t P, int32_t S, const int64_t *seg_off_dev,
+                     const int32_t *peers_dev, uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * Measurement helpers (not part of the method).
+ * cx_copy_baseline: dst[i] = src[i] for n floats (n % 4 == 0, 16-byte aligned) with the
+ * same load/store instructions as the mixing kernels; the practical HBM ceiling and the
+ * calibration kernel for the profiler's byte counters.
+ * cx_set_tuning / cx_get_tuning: process-global launch parameters for sweeps.
+ *   key 0: 16-byte slices per lane per row (1, 2, 4)      key 1: waves per workgroup (1..16)
+ *   key 2: non-temporal loads/stores (0/1)
+ * cx_set_tuning returns CX_ERR_SHAPE for an unknown key or value; a value of -1 restores
+ * the default.
+ */
+int cx_copy_baseline(const float *src, float *dst, int64_t n, void *stream);
+int cx_set_tuning(int32_t key, int32_t value);
+int cx_get_tuning(int32_t key);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CX_MIX_H */

@@ -124,13 +124,19 @@ def topology(seed: int, n: int, S: int, round0: int, R: int, mode: int = 0) -> n
 
 
 # ----------------------------------------------------------------------- mix
-def gossip_mix(x, P, seg_off, peers) -> np.ndarray:
+def gossip_mix(x, P, seg_off, peers, out=None) -> np.ndarray:
+    """`out` (optional, float32, same shape, not overlapping x) receives the result; its
+    padding columns are left as they are.  Without it a copy of x is made first."""
     x = _mat(x)
     W, ld = x.shape
     so = _seg(seg_off, P)
     S = len(so) - 1
     pe = _peers(peers, S, W)
-    out = x.copy()
+    if out is None:
+        out = x.copy()
+    elif (out.dtype != np.float32 or out.shape != x.shape or not out.flags.c_contiguous
+          or np.shares_memory(out, x)):
+        raise ValueError("out must be a separate contiguous float32 array of x's shape")
     _check(_L().oracle_gossip_mix(_p(x), _p(out), ld, W, P, S, _p(so), _p(pe)), "gossip_mix")
     return out
 

@@ -1,0 +1,174 @@
+"""Thin ctypes binding of the C-ABI library (include/cx_mix.h).
+
+Argument marshalling only: every step of the path runs inside libcxmix.so.  The
+functions carry the names of the C entry points.  Device buffers are torch tensors
+(torch provides device memory and streams, nothing else); host tables are NumPy
+arrays.  There is no CPU fallback: if the library has not been built, importing
+the symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcxmix.so")
+
+CX_MAX_ROWS = 1024
+CX_OK = 0
+STATUS = {0: "CX_OK", -1: "CX_ERR_NULL", -2: "CX_ERR_SHAPE", -3: "CX_ERR_SEGMENTS",
+          -4: "CX_ERR_PEERS", -5: "CX_ERR_ALIGN", -6: "CX_ERR_ALIAS", -7: "CX_ERR_HIP",
+          -8: "CX_ERR_UNSUPPORTED"}
+TUNE_SLICES, TUNE_WAVES, TUNE_NONTEMPORAL = 0, 1, 2
+
+EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_segments",
+           "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",
+           "cx_sgd_fused_mix", "cx_copy_baseline", "cx_set_tuning", "cx_get_tuning"]
+
+
+class CxError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed: {STATUS.get(status, status)}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it was not built (no fallback of any kind)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with "
+                          "`python -m paper_2012_15198_amd.build` (hipcc, gfx950)")
+    L = ctypes.CDLL(LIB_PATH)
+    i32, i64, u32, u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_uint64
+    f32, vp = ctypes.c_float, ctypes.c_void_p
+    L.cx_status_string.restype = ctypes.c_char_p
+    L.cx_status_string.argtypes = [ctypes.c_int]
+    L.cx_abi_version.restype = ctypes.c_int
+    L.cx_abi_version.argtypes = []
+    L.cx_topology_gen.argtypes = [u64, i32, i32, i32, i32, i32, vp]
+    L.cx_check_segments.argtypes = [vp, i32, i64]
+    L.cx_check_peers.argtypes = [vp, i32, i32]
+    L.cx_gossip_mix.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
+    L.cx_hier_mix.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, u32, vp]
+    L.cx_pushsum_mix.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, u32, vp]
+    L.cx_sgd_fused_mix.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32,
+                                   vp, vp, u32, vp]
+    L.cx_copy_baseline.argtypes = [vp, vp, i64, vp]
+    L.cx_set_tuning.argtypes = [i32, i32]
+    L.cx_get_tuning.argtypes = [i32]
+    for name in EXPORTS:
+        if name != "cx_status_string":
+            getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def _ok(fn: str, status: int) -> None:
+    if status != CX_OK:
+        raise CxError(fn, status)
+
+
+def _dptr(t) -> Optional[int]:
+    """Raw address of a torch tensor (device or host) or None."""
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _shape(x):
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("expected a row-major [W][ld] tensor (use a view of the padded matrix)")
+    return x.shape[0], x.stride(0)
+
+
+# ----------------------------------------------------------------------------- host calls
+def cx_status_string(status: int) -> str:
+    return lib().cx_status_string(status).decode()
+
+
+def cx_abi_version() -> int:
+    return lib().cx_abi_version()
+
+
+def cx_topology_gen(seed: int, n: int, S: int, round0: int, R: int, mode: int = 0,
+                    out: Optional[np.ndarray] = None) -> np.ndarray:
+    """int32 [R][S][n] peer tables on the host (see include/cx_mix.h)."""
+    if out is None:
+        out = np.empty((max(R, 0), max(S, 0), max(n, 0)), dtype=np.int32)
+    _ok("cx_topology_gen", lib().cx_topology_gen(seed & (2**64 - 1), n, S, round0, R, mode,
+                                                 out.ctypes.data))
+    return out
+
+
+def cx_check_segments(seg_off_host: np.ndarray, P: int) -> None:
+    so = np.ascontiguousarray(seg_off_host, dtype=np.int64)
+    _ok("cx_check_segments", lib().cx_check_segments(so.ctypes.data, len(so) - 1, P))
+
+
+def cx_check_peers(peers_host: np.ndarray) -> None:
+    p = np.ascontiguousarray(peers_host, dtype=np.int32)
+    if p.ndim != 2:
+        raise ValueError("expected one round's [S][n] table")
+    _ok("cx_check_peers", lib().cx_check_peers(p.ctypes.data, p.shape[0], p.shape[1]))
+
+
+def cx_set_tuning(key: int, value: int) -> None:
+    _ok("cx_set_tuning", lib().cx_set_tuning(key, value))
+
+
+def cx_get_tuning(key: int) -> int:
+    return lib().cx_get_tuning(key)
+
+
+# --------------------------------------------------------------------------- device calls
+def cx_gossip_mix(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int = 0, stream=None):
+    W, ld = _shape(x_in)
+    S = seg_off_dev.numel() - 1
+    _ok("cx_gossip_mix", lib().cx_gossip_mix(_dptr(x_in), _dptr(x_out), ld, W, P, S,
+                                             _dptr(seg_off_dev), _dptr(peers_dev), flags,
+                                             _stream(stream)))
+
+
+def cx_hier_mix(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flags: int = 0,
+                stream=None):
+    W, ld = _shape(x_in)
+    S = seg_off_dev.numel() - 1
+    _ok("cx_hier_mix", lib().cx_hier_mix(_dptr(x_in), _dptr(x_out), ld, W, P, G, S,
+                                         _dptr(seg_off_dev), _dptr(leader_peers_dev), flags,
+                                         _stream(stream)))
+
+
+def cx_pushsum_mix(x_in, x_out, w_in, w_out, z_out, P: int, hop: int, flags: int = 0,
+                   stream=None):
+    W, ld = _shape(x_in)
+    _ok("cx_pushsum_mix", lib().cx_pushsum_mix(_dptr(x_in), _dptr(x_out), _dptr(w_in),
+                                               _dptr(w_out), _dptr(z_out), ld, W, P, hop, flags,
+                                               _stream(stream)))
+
+
+def cx_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: float, P: int,
+                     seg_off_dev, peers_dev, flags: int = 0, stream=None):
+    W, ld = _shape(x_in)
+    S = seg_off_dev.numel() - 1
+    _ok("cx_sgd_fused_mix", lib().cx_sgd_fused_mix(_dptr(x_in), _dptr(x_out), _dptr(v_in),
+                                                   _dptr(v_out), _dptr(g), lr, mu, wd, ld, W, P,
+                                                   S, _dptr(seg_off_dev), _dptr(peers_dev), flags,
+                                                   _stream(stream)))
+
+
+def cx_copy_baseline(src, dst, stream=None):
+    _ok("cx_copy_baseline", lib().cx_copy_baseline(_dptr(src), _dptr(dst), src.numel(),
+                                                   _stream(stream)))

@@ -1,0 +1,43 @@
+"""Helpers shared by the GPU parity tests (marshalling only)."""
+import numpy as np
+import torch
+
+from paper_2012_15198_amd import cxmix as cx
+
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def bits(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def same_bits(a, b):
+    """Bit equality, except that any NaN matches any NaN (payloads are not specified)."""
+    a, b = np.ascontiguousarray(a), np.ascontiguousarray(b)
+    return bool(((bits(a) == bits(b)) | (np.isnan(a) & np.isnan(b))).all())
+
+
+class Tuning:
+    """Context manager: set the library's launch parameters, restore defaults after."""
+
+    def __init__(self, slices=-1, waves=-1, nt=-1):
+        self.v = (slices, waves, nt)
+
+    def __enter__(self):
+        for k, v in enumerate(self.v):
+            cx.cx_set_tuning(k, v)
+
+    def __exit__(self, *exc):
+        for k in range(3):
+            cx.cx_set_tuning(k, -1)
+
+
+ALL_TUNINGS = [(-1, -1, -1), (1, 1, 0), (2, 2, 1), (4, 8, 0), (1, 4, 1), (2, 3, 0)]

@@ -1,0 +1,288 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Sizes span several wave tiles (256..1024 columns each), unaligned segment
+boundaries and a ragged row end.  Bars: bit-exact for the pairwise average (and for the
+fixed-order fp32 variants); 1e-6 relative against the fp64 reference for hierarchical,
+fused and push-sum results."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2012_15198_amd import cxmix as cx
+from paper_2012_15198_amd import workloads as WL
+from gpu_util import ALL_TUNINGS, Tuning, bits, dev, host, same_bits
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-6
+
+
+def run_gossip(x, P, so, pe, inplace):
+    xd = dev(x)
+    out = xd if inplace else torch.full_like(xd, float("nan"))
+    if not inplace:
+        out[:, P:] = xd[:, P:]
+    cx.cx_gossip_mix(xd, out, P, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    return host(out)
+
+
+@pytest.mark.parametrize("W,P,ld,S", [(2, 1, 4, 1), (2, 7, 8, 2), (3, 1024, 1024, 1), (8, 5003, 5004, 4),
+                                      (5, 4099, 4224, 7), (33, 9001, 9004, 8), (8, 2500, 2500, 3),
+                                      (64, 3000, 3008, 5), (130, 1500, 1500, 2)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_gossip_bit_exact(W, P, ld, S, inplace):
+    x = WL.gen_matrix(W, P, 1.0, seed=W * 1000 + P, ld=ld)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(7, W, S, 0, 1)[0]
+    want = O.gossip_mix(x, P, so, pe)
+    got = run_gossip(x, P, so, pe, inplace)
+    assert same_bits(got, want)          # includes the untouched padding columns
+
+
+@pytest.mark.parametrize("tuning", ALL_TUNINGS)
+def test_gossip_bit_exact_under_every_launch_shape(tuning):
+    W, P, ld, S = 12, 7777, 7780, 6
+    x = WL.gen_matrix(W, P, 1.0, seed=5, ld=ld)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(5, W, S, 0, 3)
+    want = x
+    for r in range(3):
+        want = O.gossip_mix(want, P, so, tabs[r])
+    with Tuning(*tuning):
+        xd, sod = dev(x), dev(so)
+        for r in range(3):
+            cx.cx_gossip_mix(xd, xd, P, sod, dev(tabs[r]))
+        torch.cuda.synchronize()
+    assert same_bits(host(xd), want)
+
+
+def test_gossip_edge_values_signed_zero_subnormal_overflow():
+    W, P = 6, 3001
+    x = np.stack([WL.edge_values(P, seed=i) for i in range(W)])
+    x = np.pad(x, ((0, 0), (0, 3)), constant_values=7.0)
+    so = WL.equal_seg_off(P, 3)
+    pe = O.topology(1, W, 3, 0, 1)[0]
+    with np.errstate(all="ignore"):
+        want = O.gossip_mix(x, P, so, pe)
+    for inplace in (False, True):
+        assert same_bits(run_gossip(x, P, so, pe, inplace), want)
+
+
+def test_gossip_ragged_and_degenerate_segments():
+    W, P, ld = 7, 6000, 6000
+    x = WL.gen_matrix(W, P, 1.0, seed=21, ld=ld)
+    # tiny, empty, unaligned and tile-sized segments in one table; many inside one tile
+    so = np.array([0, 1, 1, 2, 5, 5, 9, 1023, 1024, 1025, 2048, 2051, 5999, 6000], dtype=np.int64)
+    S = len(so) - 1
+    pe = O.topology(3, W, S, 0, 1)[0]
+    want = O.gossip_mix(x, P, so, pe)
+    for tuning in [(-1, -1, -1), (1, 2, 1)]:
+        with Tuning(*tuning):
+            assert same_bits(run_gossip(x, P, so, pe, True), want)
+    # one segment per column
+    P2 = 300
+    x2 = WL.gen_matrix(4, P2, 1.0, seed=22, ld=P2)
+    so2 = np.arange(P2 + 1, dtype=np.int64)
+    pe2 = O.topology(4, 4, P2, 0, 1)[0]
+    assert same_bits(run_gossip(x2, P2, so2, pe2, False), O.gossip_mix(x2, P2, so2, pe2))
+
+
+def test_gossip_max_rows():
+    W, P = cx.CX_MAX_ROWS, 520
+    x = WL.gen_matrix(W, P, 1.0, seed=23)
+    so = WL.equal_seg_off(P, 2)
+    pe = O.topology(23, W, 2, 0, 1)[0]
+    assert same_bits(run_gossip(x, P, so, pe, True), O.gossip_mix(x, P, so, pe))
+
+
+def test_table_that_is_not_a_permutation_means_no_mixing_for_that_segment():
+    W, P = 4, 2000
+    x = WL.gen_matrix(W, P, 1.0, seed=24)
+    so = np.array([0, 700, 1400, 2000], dtype=np.int64)
+    good = O.topology(24, W, 3, 0, 1)[0]
+    bad = good.copy()
+    bad[1] = [1, 1, 2, 3]          # duplicate
+    bad[2] = [1, 2, 3, 9]          # out of range
+    ref = bad.copy()
+    ref[1] = ref[2] = np.arange(W)
+    assert same_bits(run_gossip(x, P, so, bad, True), O.gossip_mix(x, P, so, ref))
+    assert same_bits(run_gossip(x, P, so, bad, False), O.gossip_mix(x, P, so, ref))
+
+
+def test_deterministic_and_inplace_equals_pingpong_over_rounds():
+    W, P, S, R = 16, 10007, 5, 6
+    x = WL.gen_matrix(W, P, 1.0, seed=25, ld=10008)
+    sod = dev(WL.equal_seg_off(P, S))
+    tabs = [dev(t) for t in O.topology(25, W, S, 0, R)]
+    a = dev(x)
+    b0, b1 = dev(x), torch.full((W, 10008), float("nan"), device=a.device)
+    b1[:, P:] = b0[:, P:]
+    for r in range(R):
+        cx.cx_gossip_mix(a, a, P, sod, tabs[r])
+        cx.cx_gossip_mix(b0, b1, P, sod, tabs[r])
+        b0, b1 = b1, b0
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int32), b0.view(torch.int32))
+    c = dev(x)
+    for r in range(R):
+        cx.cx_gossip_mix(c, c, P, sod, tabs[r])
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int32), c.view(torch.int32))
+
+
+# ------------------------------------------------------------------------ hierarchical
+def hier_tol(x, G, P, y64, pe, so):
+    """1e-6 relative to max(|ref|, mean |x| over the rows that enter the result)."""
+    W = x.shape[0]
+    L = W // G
+    a = np.abs(x[:, :P].astype(np.float64)).reshape(L, G, P).mean(1)       # [L][P]
+    scale = a.copy()
+    if L > 1:
+        for s in range(len(so) - 1):
+            c0, c1 = so[s], so[s + 1]
+            scale[:, c0:c1] = 0.5 * (a[:, c0:c1] + a[pe[s], c0:c1])
+    scale = np.repeat(scale, G, axis=0)
+    return REL * np.maximum(np.abs(y64[:, :P]), scale)
+
+
+@pytest.mark.parametrize("W,G,P,ld,S", [(8, 1, 3001, 3004, 3), (8, 2, 3001, 3004, 3), (16, 4, 5003, 5004, 4),
+                                        (64, 8, 4099, 4100, 16), (32, 16, 2600, 2600, 2),
+                                        (8, 8, 2100, 2100, 3), (16, 16, 1030, 1032, 1), (2, 2, 5, 8, 1)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_hier_matches_fp64_reference_and_fixed_order_fp32(W, G, P, ld, S, inplace):
+    x = WL.gen_matrix(W, P, 0.05, seed=W + G + P, ld=ld)
+    so = WL.equal_seg_off(P, S)
+    L = W // G
+    pe = O.topology(9, L, S, 0, 1)[0] if L > 1 else None
+    xd = dev(x)
+    out = xd if inplace else xd.clone()
+    cx.cx_hier_mix(xd, out, P, G, dev(so), dev(pe) if pe is not None else None)
+    torch.cuda.synchronize()
+    got = host(out)
+    y64 = O.hier_mix_f64(x, P, G, so, pe)
+    assert (np.abs(got[:, :P] - y64[:, :P]) <= hier_tol(x, G, P, y64, pe, so)).all()
+    assert same_bits(got, O.hier_mix_f32(x, P, G, so, pe))
+    assert same_bits(got[:, P:], x[:, P:])
+
+
+@pytest.mark.parametrize("tuning", ALL_TUNINGS)
+def test_hier_rounds_under_every_launch_shape(tuning):
+    W, G, P, S, R = 32, 8, 6007, 5, 3
+    x = WL.gen_matrix(W, P, 0.05, seed=31, ld=6008)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(31, W // G, S, 0, R)
+    want = x
+    for r in range(R):
+        want = O.hier_mix_f32(want, P, G, so, tabs[r])
+    with Tuning(*tuning):
+        xd = dev(x)
+        for r in range(R):
+            cx.cx_hier_mix(xd, xd, P, G, dev(so), dev(tabs[r]))
+        torch.cuda.synchronize()
+    assert same_bits(host(xd), want)
+
+
+# --------------------------------------------------------------------------- fused SGD
+@pytest.mark.parametrize("W,P,ld,S", [(2, 9, 12, 2), (8, 5003, 5004, 4), (33, 3100, 3100, 3)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_fused_matches_fp64_reference_and_fixed_order_fp32(W, P, ld, S, inplace):
+    lr, mu, wd = 0.1, 0.9, 1e-4
+    x = WL.gen_matrix(W, P, 0.05, seed=41, ld=ld)
+    v = WL.gen_matrix(W, P, 0.01, seed=41, ld=ld, stream=1)
+    g = WL.gen_matrix(W, P, 0.01, seed=41, ld=ld, stream=2)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(41, W, S, 0, 1)[0]
+    xd, vd, gd = dev(x), dev(v), dev(g)
+    xo = xd if inplace else xd.clone()
+    vo = vd if inplace else vd.clone()
+    cx.cx_sgd_fused_mix(xd, xo, vd, vo, gd, lr, mu, wd, P, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    gx, gv = host(xo), host(vo)
+    x64, v64 = O.sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, so, pe)
+    ax = np.abs(x[:, :P].astype(np.float64))
+    xscale = ax.copy()
+    for s in range(S):
+        xscale[:, so[s]:so[s + 1]] = np.maximum(ax[:, so[s]:so[s + 1]], ax[pe[s], so[s]:so[s + 1]])
+    assert (np.abs(gx[:, :P] - x64[:, :P]) <= REL * np.maximum(np.abs(x64[:, :P]), xscale)).all()
+    vscale = np.maximum(np.abs(v[:, :P]), np.abs(g[:, :P])).astype(np.float64)
+    assert (np.abs(gv[:, :P] - v64[:, :P]) <= REL * np.maximum(np.abs(v64[:, :P]), vscale)).all()
+    x32, v32 = O.sgd_fused_mix_f32(x, v, g, lr, mu, wd, P, so, pe)
+    assert same_bits(gx, x32) and same_bits(gv, v32)
+    assert same_bits(host(gd), g)
+
+
+def test_fused_lr0_is_gossip_and_rounds_track_oracle():
+    W, P, S, R = 8, 4001, 4, 4
+    lr, mu, wd = 0.1, 0.9, 1e-4
+    x = WL.gen_matrix(W, P, 0.05, seed=42, ld=4004)
+    v = np.zeros_like(x)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(42, W, S, 0, R)
+    xd, vd = dev(x), dev(v)
+    wx, wv = x, v
+    for r in range(R):
+        g = WL.gen_matrix(W, P, 0.01, seed=42, ld=4004, stream=10 + r)
+        cx.cx_sgd_fused_mix(xd, xd, vd, vd, dev(g), lr, mu, wd, P, dev(so), dev(tabs[r]))
+        wx, wv = O.sgd_fused_mix_f32(wx, wv, g, lr, mu, wd, P, so, tabs[r])
+    torch.cuda.synchronize()
+    assert same_bits(host(xd), wx) and same_bits(host(vd), wv)
+    x0 = dev(x)
+    cx.cx_sgd_fused_mix(x0, x0, dev(v), dev(v), dev(x), 0.0, mu, wd, P, dev(so), dev(tabs[0]))
+    torch.cuda.synchronize()
+    assert same_bits(host(x0), O.gossip_mix(x, P, so, tabs[0]))
+
+
+# ---------------------------------------------------------------------------- push-sum
+@pytest.mark.parametrize("W,P,ld,hop", [(2, 5, 8, 1), (8, 5003, 5004, 1), (8, 5003, 5004, 4),
+                                        (6, 3000, 3000, 4), (128, 1100, 1100, 64), (13, 2049, 2052, 8)])
+@pytest.mark.parametrize("inplace", [False, True])
+@pytest.mark.parametrize("want_z", [False, True])
+def test_pushsum_matches_reference(W, P, ld, hop, inplace, want_z):
+    x = WL.gen_matrix(W, P, 0.05, seed=51, ld=ld)
+    w = (1.0 + 0.5 * np.random.default_rng(51).random(W)).astype(np.float32)
+    xd, wd_ = dev(x), dev(w)
+    xo = xd if inplace else xd.clone()
+    wo = torch.zeros_like(wd_)
+    z = torch.full_like(xd, 777.0) if want_z else None
+    cx.cx_pushsum_mix(xd, xo, wd_, wo, z, P, hop)
+    torch.cuda.synchronize()
+    x32, w32, z32 = O.pushsum_mix_f32(x, w, P, hop, want_z)
+    x64, w64, z64 = O.pushsum_mix_f64(x, w, P, hop, want_z)
+    gx, gw = host(xo), host(wo)
+    assert same_bits(gx, x32) and same_bits(gw, w32)
+    ax = np.abs(x[:, :P].astype(np.float64))
+    scale = np.maximum(ax, np.roll(ax, hop, axis=0))
+    assert (np.abs(gx[:, :P] - x64[:, :P]) <= REL * np.maximum(np.abs(x64[:, :P]), scale)).all()
+    assert (np.abs(gw - w64) <= REL * np.abs(w64)).all()
+    if want_z:
+        gz = host(z)
+        assert (np.abs(gz[:, :P] - z64[:, :P]) <=
+                REL * np.maximum(np.abs(z64[:, :P]), scale / w64[:, None])).all()
+        assert same_bits(gz[:, :P], z32[:, :P])
+        assert (gz[:, P:] == 777.0).all()
+
+
+def test_pushsum_log2w_hops_reach_the_mean_and_keep_unit_weight():
+    W, P = 128, 2050
+    x = WL.gen_matrix(W, P, 0.05, seed=52, ld=2052)
+    mean = x[:, :P].astype(np.float64).mean(0)
+    xd = dev(x)
+    w0, w1 = torch.ones(W, device=xd.device), torch.zeros(W, device=xd.device)
+    for k in range(7):
+        cx.cx_pushsum_mix(xd, xd, w0, w1, None, P, 2 ** k)
+        w0, w1 = w1, w0
+    torch.cuda.synchronize()
+    assert (host(w0) == 1.0).all()
+    assert np.abs(host(xd)[:, :P] - mean).max() <= 1e-6 * np.abs(x).max()
+
+
+def test_copy_baseline_copies():
+    n = 4 * 100003
+    src = torch.randn(n, device="cuda:0")
+    for tuning in ALL_TUNINGS:
+        with Tuning(*tuning):
+            dst = torch.zeros_like(src)
+            cx.cx_copy_baseline(src, dst)
+            torch.cuda.synchronize()
+            assert torch.equal(src, dst)

@@ -1,0 +1,136 @@
+"""CPU-only tests of the library's host half: it loads, exports every declared symbol,
+generates the same topology as the oracle, validates tables and rejects bad arguments
+before touching a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2012_15198_amd import cxmix as cx
+from paper_2012_15198_amd import workloads as WL
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_symbol_the_header_declares():
+    header = open(os.path.join(ROOT, "include", "cx_mix.h")).read()
+    declared = set(re.findall(r"\b(cx_[a-z_]+)\s*\(", header))
+    assert declared == set(cx.EXPORTS)
+    L = cx.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert cx.cx_abi_version() == 1
+    assert cx.cx_status_string(0) == "CX_OK" and cx.cx_status_string(-6) == "CX_ERR_ALIAS"
+    for code, name in cx.STATUS.items():
+        assert cx.cx_status_string(code) == name
+
+
+@pytest.mark.parametrize("n,S,R,seed", [(2, 1, 5, 0), (3, 4, 200, 1), (8, 4, 10, 1), (32, 8, 50, 2),
+                                        (8, 16, 20, 3), (128, 8, 20, 4), (32, 32, 10, 5),
+                                        (1024, 2, 2, 9), (7, 3, 40, 2**64 - 1), (6, 5, 300, 123)])
+def test_topology_is_bit_exact_against_the_oracle(n, S, R, seed):
+    assert (cx.cx_topology_gen(seed, n, S, 0, R) == O.topology(seed, n, S, 0, R)).all()
+    assert (cx.cx_topology_gen(seed, n, S, 4, R, 1) == O.topology(seed, n, S, 4, R, 1)).all()
+    # resume: a later window is the tail of the full run
+    full = cx.cx_topology_gen(seed, n, S, 0, R)
+    assert (cx.cx_topology_gen(seed, n, S, R // 2, R - R // 2) == full[R // 2:]).all()
+    for tab in full[:5]:
+        cx.cx_check_peers(tab)
+
+
+def test_topology_argument_errors():
+    out = np.zeros((1, 1, 4), dtype=np.int32)
+    L = cx.lib()
+    assert L.cx_topology_gen(0, 4, 1, 0, 1, 0, None) == -1
+    assert L.cx_topology_gen(0, 1, 1, 0, 1, 0, out.ctypes.data) == -2
+    assert L.cx_topology_gen(0, cx.CX_MAX_ROWS + 1, 1, 0, 1, 0, out.ctypes.data) == -2
+    assert L.cx_topology_gen(0, 4, 0, 0, 1, 0, out.ctypes.data) == -2
+    assert L.cx_topology_gen(0, 4, 1, -1, 1, 0, out.ctypes.data) == -2
+    assert L.cx_topology_gen(0, 4, 1, 0, -1, 0, out.ctypes.data) == -2
+    assert L.cx_topology_gen(0, 4, 1, 2**31 - 1, 1, 0, out.ctypes.data) == -2
+    assert L.cx_topology_gen(0, 4, 1, 0, 1, 7, out.ctypes.data) == -8
+    assert L.cx_topology_gen(0, 4, 1, 0, 0, 0, out.ctypes.data) == 0     # R = 0 writes nothing
+
+
+def test_check_segments_and_peers():
+    cx.cx_check_segments(WL.equal_seg_off(100, 7), 100)
+    cx.cx_check_segments(np.array([0, 0, 50, 50, 100]), 100)            # empty segments are fine
+    for bad in ([1, 50, 100], [0, 60, 50, 100], [0, 50, 99]):
+        with pytest.raises(cx.CxError) as e:
+            cx.cx_check_segments(np.array(bad), 100)
+        assert e.value.status == -3
+    cx.cx_check_peers(np.array([[1, 2, 0], [2, 0, 1]]))
+    for bad in ([[0, 2, 1]], [[1, 1, 0]], [[1, 2, 3]], [[-1, 2, 0]]):
+        with pytest.raises(cx.CxError) as e:
+            cx.cx_check_peers(np.array(bad))
+        assert e.value.status == -4
+
+
+def test_mix_calls_reject_bad_arguments_on_the_host():
+    """Every error below is detected before any HIP call, so it runs without a GPU.
+    Fake but well-aligned addresses stand in for device buffers."""
+    L = cx.lib()
+    A, B, C, D, E = 0x10000000, 0x20000000, 0x30000000, 0x40000000, 0x50000000
+    T1, T2 = 0x60000000, 0x60001000
+    ok = dict(x_in=A, x_out=B, ld=64, W=4, P=60, S=2, so=T1, pe=T2, flags=0, st=None)
+
+    def gossip(**kw):
+        a = {**ok, **kw}
+        return L.cx_gossip_mix(a["x_in"], a["x_out"], a["ld"], a["W"], a["P"], a["S"], a["so"],
+                               a["pe"], a["flags"], a["st"])
+
+    assert gossip(x_in=None) == -1 and gossip(x_out=None) == -1
+    assert gossip(so=None) == -1 and gossip(pe=None) == -1
+    assert gossip(W=1) == -2 and gossip(W=cx.CX_MAX_ROWS + 1) == -2
+    assert gossip(S=0) == -2 and gossip(P=0) == -2 and gossip(ld=56) == -2
+    assert gossip(ld=62, P=60) == -5 and gossip(x_in=A + 4) == -5 and gossip(x_out=B + 8) == -5
+    assert gossip(x_out=A + 64) == -6                       # partial overlap
+    assert gossip(flags=1) == -8
+
+    def hier(G=2, pe=T2, **kw):
+        a = {**ok, **kw}
+        return L.cx_hier_mix(a["x_in"], a["x_out"], a["ld"], a["W"], a["P"], G, a["S"], a["so"],
+                             pe, a["flags"], a["st"])
+
+    assert hier(G=0) == -2 and hier(G=3) == -2 and hier(x_in=None) == -1
+    assert hier(pe=None) == -1                              # L = 2 needs a table
+    assert hier(G=1, W=cx.CX_MAX_ROWS + 1) == -2
+    assert hier(G=32, W=64) == -8                           # group size this build lacks
+    assert hier(x_out=A + 16) == -6
+
+    def push(hop=1, w_in=C, w_out=D, z=None, **kw):
+        a = {**ok, **kw}
+        return L.cx_pushsum_mix(a["x_in"], a["x_out"], w_in, w_out, z, a["ld"], a["W"], a["P"],
+                                hop, a["flags"], a["st"])
+
+    assert push(hop=0) == -2 and push(hop=4) == -2 and push(w_in=None) == -1
+    assert push(w_out=C) == -6 and push(w_out=C + 8) == -6
+    assert push(z=A) == -6 and push(z=B) == -6 and push(z=E + 4) == -5
+
+    def fused(v_in=C, v_out=C, g=D, **kw):
+        a = {**ok, **kw}
+        return L.cx_sgd_fused_mix(a["x_in"], a["x_out"], v_in, v_out, g, 0.1, 0.9, 1e-4, a["ld"],
+                                  a["W"], a["P"], a["S"], a["so"], a["pe"], a["flags"], a["st"])
+
+    assert fused(g=None) == -1 and fused(v_in=None) == -1
+    assert fused(v_in=A) == -6 and fused(v_out=B) == -6 and fused(g=B) == -6
+    assert fused(v_out=C + 32) == -6 and fused(g=D + 4) == -5 and fused(W=1) == -2
+
+    assert L.cx_copy_baseline(None, B, 64, None) == -1
+    assert L.cx_copy_baseline(A, B, 6, None) == -2
+    assert L.cx_copy_baseline(A, A + 64, 64, None) == -6
+
+
+def test_tuning_keys():
+    for key, good, bad in [(cx.TUNE_SLICES, 2, 3), (cx.TUNE_WAVES, 8, 17), (cx.TUNE_NONTEMPORAL, 0, 2)]:
+        cx.cx_set_tuning(key, good)
+        assert cx.cx_get_tuning(key) == good
+        with pytest.raises(cx.CxError):
+            cx.cx_set_tuning(key, bad)
+        cx.cx_set_tuning(key, -1)
+        assert cx.cx_get_tuning(key) == -1
+    with pytest.raises(cx.CxError):
+        cx.cx_set_tuning(9, 1)
