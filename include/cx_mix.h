@@ -152,8 +152,9 @@ int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *
  * same load/store instructions as the mixing kernels; the practical HBM ceiling and the
  * calibration kernel for the profiler's byte counters.
  * cx_set_tuning / cx_get_tuning: process-global launch parameters for sweeps.
- *   key 0: 16-byte slices per lane per row (1, 2, 4)      key 1: waves per workgroup (1..16)
- *   key 2: non-temporal loads/stores (0/1)
+ *   key 0: 16-byte slices per lane per row (1, 2, 4)      key 1: waves per workgroup (1..8) 
+ *   key 2: non-temporal loads/stores (0/1)                key 3: rows in flight per lane (2, 4, 8)
+ * A (key 0, key 3) pair that an operator was not built with falls back to its default.
  * cx_set_tuning returns CX_ERR_SHAPE for an unknown key or value; a value of -1 restores
  * the default.
  */

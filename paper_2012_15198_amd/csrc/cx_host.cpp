@@ -63,7 +63,8 @@ void fair_table(const DrawStream &rng, int32_t n, int32_t *recv_from, std::vecto
     }
 }
 
-std::atomic<int32_t> g_tuning[3] = {{-1}, {-1}, {-1}};
+constexpr int kTuningKeys = 8;
+std::atomic<int32_t> g_tuning[kTuningKeys] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
 
 }  // namespace
 
@@ -145,11 +146,14 @@ int cx_check_peers(const int32_t *peers_host, int32_t S, int32_t n)
 
 int cx_set_tuning(int32_t key, int32_t value)
 {
-    if (key < 0 || key > 2) return CX_ERR_SHAPE;
+    if (key < 0 || key >= kTuningKeys) return CX_ERR_SHAPE;
     if (value != -1) {
         if (key == 0 && value != 1 && value != 2 && value != 4) return CX_ERR_SHAPE;
-        if (key == 1 && (value < 1 || value > 16)) return CX_ERR_SHAPE;
+        if (key == 1 && (value < 1 || value > 8)) return CX_ERR_SHAPE;
         if (key == 2 && value != 0 && value != 1) return CX_ERR_SHAPE;
+        if (key == 3 && value != 2 && value != 4 && value != 8) return CX_ERR_SHAPE;
+        if ((key == 4 || key == 5 || key == 7) && value != 0 && value != 1) return CX_ERR_SHAPE;
+        if (key == 6 && (value < 1 || value > 4096)) return CX_ERR_SHAPE;
     }
     g_tuning[key].store(value);
     return CX_OK;
@@ -157,7 +161,7 @@ int cx_set_tuning(int32_t key, int32_t value)
 
 int cx_get_tuning(int32_t key)
 {
-    if (key < 0 || key > 2) return CX_ERR_SHAPE;
+    if (key < 0 || key >= kTuningKeys) return CX_ERR_SHAPE;
     return g_tuning[key].load();
 }
 

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #pragma clang fp contract(off)
 
@@ -50,6 +51,16 @@ struct Tile {
 };
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Compile-time loop: f(integral_constant<int, I>) for I in [I0, N).
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 // Orders LDS traffic between the lanes of ONE wavefront (wave-private LDS regions).
 __device__ __forceinline__ void wave_sync()
@@ -116,25 +127,33 @@ __device__ __forceinline__ Tile<U> tree_sum(const Tile<U> *r)
 // ---------------------------------------------------------------------------------
 // Row operators: what "load gossiping row r" and "store gossiping row r" mean.
 // ---------------------------------------------------------------------------------
+// Each operator splits "load gossiping row r" into issue() -- put the row's global loads in
+// flight into a Raw slot -- and finish() -- turn the arrived data into the tile that takes
+// part in the pairwise average.  kRawPerSlice = 16-byte registers per slice and slot.
 // Plain gossip (G == 1) and hierarchical mode (a gossiping row = a group of G rows).
 template <int G>
 struct MeanOp {
+    static constexpr int kRawPerSlice = G;
+    template <int U> struct Raw { Tile<U> r[G]; };
     const float *xin;
     float *xout;
     int64_t ld;
     float inv_g;
 
     template <int U, bool FULL, bool NT>
-    __device__ __forceinline__ void load(int row, int64_t off, const unsigned (&mask)[U], Tile<U> &t) const
+    __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
     {
         const float *p = xin + static_cast<int64_t>(row) * G * ld + off;
-        if constexpr (G == 1) {
-            tile_load<U, FULL, NT>(p, mask, t);
-        } else {
-            Tile<U> r[G];
 #pragma unroll
-            for (int j = 0; j < G; ++j) tile_load<U, FULL, NT>(p + j * ld, mask, r[j]);
-            t = tree_sum<G, U>(r);
+        for (int j = 0; j < G; ++j) tile_load<U, FULL, NT>(p + j * ld, mask, raw.r[j]);
+    }
+    template <int U, bool FULL, bool NT, bool COMMIT = true>
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Tile<U> &t) const
+    {
+        if constexpr (G == 1) {
+            t = raw.r[0];
+        } else {
+            t = tree_sum<G, U>(raw.r);
 #pragma unroll
             for (int u = 0; u < U; ++u) t.v[u] = t.v[u] * inv_g;
         }
@@ -148,8 +167,10 @@ struct MeanOp {
     }
 };
 
-// Momentum-SGD applied while the row is loaded; the walk then mixes the updated rows.
+// Momentum-SGD applied as the row arrives; the walk then mixes the updated rows.
 struct FusedOp {
+    static constexpr int kRawPerSlice = 3;
+    template <int U> struct Raw { Tile<U> x, v, g; };
     const float *xin;
     float *xout;
     const float *vin;
@@ -159,20 +180,25 @@ struct FusedOp {
     float lr, mu, wd;
 
     template <int U, bool FULL, bool NT>
-    __device__ __forceinline__ void load(int row, int64_t off, const unsigned (&mask)[U], Tile<U> &t) const
+    __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
     {
         const int64_t o = static_cast<int64_t>(row) * ld + off;
-        Tile<U> x, v, gr;
-        tile_load<U, FULL, NT>(xin + o, mask, x);
-        tile_load<U, FULL, NT>(vin + o, mask, v);
-        tile_load<U, FULL, NT>(g + o, mask, gr);
+        tile_load<U, FULL, NT>(xin + o, mask, raw.x);
+        tile_load<U, FULL, NT>(vin + o, mask, raw.v);
+        tile_load<U, FULL, NT>(g + o, mask, raw.g);
+    }
+    // COMMIT: also write v' of this row (false when the row is only recomputed as a partner)
+    template <int U, bool FULL, bool NT, bool COMMIT = true>
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Tile<U> &t) const
+    {
+        Tile<U> v;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const f4 decayed = gr.v[u] + x.v[u] * wd;     // g' = g + wd*x
-            v.v[u] = v.v[u] * mu + decayed;               // v' = mu*v + g'
-            t.v[u] = x.v[u] - v.v[u] * lr;                // x_half = x - lr*v'
+            const f4 decayed = raw.g.v[u] + raw.x.v[u] * wd;   // g' = g + wd*x
+            v.v[u] = raw.v.v[u] * mu + decayed;                // v' = mu*v + g'
+            t.v[u] = raw.x.v[u] - v.v[u] * lr;                 // x_half = x - lr*v'
         }
-        tile_store<U, FULL, NT>(vout + o, mask, v);
+        if constexpr (COMMIT) tile_store<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v);
     }
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Tile<U> &t) const
@@ -183,6 +209,8 @@ struct FusedOp {
 
 // Push-sum: plain rows, optional de-biased copy z = x' / w'.
 struct PushOp {
+    static constexpr int kRawPerSlice = 1;
+    template <int U> struct Raw { Tile<U> x; };
     const float *xin;
     float *xout;
     float *zout;          // may be null
@@ -191,9 +219,14 @@ struct PushOp {
     int n, hop;
 
     template <int U, bool FULL, bool NT>
-    __device__ __forceinline__ void load(int row, int64_t off, const unsigned (&mask)[U], Tile<U> &t) const
+    __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
     {
-        tile_load<U, FULL, NT>(xin + static_cast<int64_t>(row) * ld + off, mask, t);
+        tile_load<U, FULL, NT>(xin + static_cast<int64_t>(row) * ld + off, mask, raw.x);
+    }
+    template <int U, bool FULL, bool NT, bool COMMIT = true>
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Tile<U> &t) const
+    {
+        t = raw.x;
     }
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Tile<U> &t) const
@@ -256,53 +289,102 @@ __device__ __forceinline__ void build_schedule(int *tab, int *sched, int n, int 
     wave_sync();
 }
 
-// One lane's walk over all cycles of the schedule.
-template <class Op, int U, bool FULL, bool NT>
+// One lane's walk over all cycles of the schedule, software-pipelined: the global loads of
+// the rows of steps k+2 .. k+1+D are in flight while step k is averaged and stored.  Rows
+// are fetched in schedule order, each exactly once, into a ring of D register slots
+// (statically indexed: the step loop is unrolled by D).  Loads are always issued ahead of
+// the store of the current row, so a load never waits behind a store's acknowledgement.
+template <class Op, int U, int D, bool FULL, bool NT, bool SYNC = false>
 __device__ __forceinline__ void walk(const Op &op, const int *sched, int n, bool skip_mix,
                                      int64_t off, const unsigned (&mask)[U])
 {
-    int k = 0;
-    while (k < n) {
-        int e = uniform(sched[k]);
-        Tile<U> cur;
-        op.template load<U, FULL, NT>(e & kRowMask, off, mask, cur);
-        const Tile<U> first = cur;
-        for (;;) {
-            const bool last = (e & kLastBit) != 0;
-            Tile<U> nxt;
-            int e2 = 0;
-            if (!last) {
-                e2 = uniform(sched[k + 1]);
-                op.template load<U, FULL, NT>(e2 & kRowMask, off, mask, nxt);
-            } else {
-                nxt = first;
-            }
-            Tile<U> out;
+    typename Op::template Raw<U> slot[D];
 #pragma unroll
-            for (int u = 0; u < U; ++u) out.v[u] = skip_mix ? cur.v[u] : (cur.v[u] + nxt.v[u]) * 0.5f;
-            op.template store<U, FULL, NT>(e & kRowMask, off, mask, out);
-            ++k;
-            if (last) break;
-            cur = nxt;
-            e = e2;
-        }
+    for (int j = 0; j < D; ++j)
+        if (j < n) op.template issue<U, FULL, NT>(uniform(sched[j]) & kRowMask, off, mask, slot[j]);
+
+    int e = uniform(sched[0]);
+    Tile<U> cur;
+    op.template finish<U, FULL, NT>(e & kRowMask, off, mask, slot[0], cur);
+    if (D < n) op.template issue<U, FULL, NT>(uniform(sched[D]) & kRowMask, off, mask, slot[0]);
+    if (skip_mix) {                       // a single gossiping row: nothing to average with
+        op.template store<U, FULL, NT>(e & kRowMask, off, mask, cur);
+        return;
+    }
+    Tile<U> first = cur;
+    for (int base = 0; base < n; base += D) {
+        static_for<0, D>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            constexpr int kNextSlot = (j + 1) % D;
+            const int k = base + j;
+            if (k < n) {
+                if constexpr (SYNC) __syncthreads();   // the workgroup visits each row together
+                Tile<U> nx;
+                int e1 = 0;
+                if (k + 1 < n) {          // row of step k+1 arrives; its slot is refilled at once
+                    e1 = uniform(sched[k + 1]);
+                    op.template finish<U, FULL, NT>(e1 & kRowMask, off, mask, slot[kNextSlot], nx);
+                    if (k + 1 + D < n)
+                        op.template issue<U, FULL, NT>(uniform(sched[k + 1 + D]) & kRowMask, off, mask,
+                                                       slot[kNextSlot]);
+                }
+                const bool last = (e & kLastBit) != 0;      // row k closes its cycle
+                Tile<U> out;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const f4 partner = last ? first.v[u] : nx.v[u];
+                    out.v[u] = (cur.v[u] + partner) * 0.5f;
+                }
+                op.template store<U, FULL, NT>(e & kRowMask, off, mask, out);
+                if (last) first = nx;                       // step k+1 opens the next cycle
+                cur = nx;
+                e = e1;
+            }
+        });
     }
 }
 
-template <class Op, int U, bool NT>
+template <class Op, int U, int D, bool NT>
 __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
     Op op, int n, int64_t P, int S, const int64_t *__restrict__ seg_off,
-    const int32_t *__restrict__ peers, int shift, int skip_mix, int64_t ntiles)
+    const int32_t *__restrict__ peers, int shift, int skip_mix, int64_t ntiles, int lockstep)
 {
     extern __shared__ int lds[];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = uniform(threadIdx.x >> 6);
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;
-    if (tile >= ntiles) return;                 // waves are independent: no block barrier anywhere
+    const int nwaves = blockDim.x >> 6;
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * nwaves + wave;
+    constexpr int kTileCols = 256 * U;
+
+    if (lockstep) {
+        // Workgroup-uniform fast path: the whole super-tile of the workgroup lies inside one
+        // segment, so its waves share one schedule and walk the rows in lock-step.
+        const int64_t g0 = static_cast<int64_t>(blockIdx.x) * nwaves * kTileCols;
+        const int64_t g1 = g0 + static_cast<int64_t>(nwaves) * kTileCols;
+        int lo = 1, hi = S;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (seg_off[mid] <= g0) lo = mid + 1; else hi = mid;
+        }
+        const int s = lo - 1;
+        const int64_t b = (s == 0) ? 0 : seg_off[s];
+        const int64_t e = (s == S - 1) ? P : seg_off[s + 1];
+        if (g1 <= P && b <= g0 && e >= g1) {
+            int *tab = lds;
+            int *sched = lds + n;
+            if (wave == 0) build_schedule(tab, sched, n, lane, peers, s, shift);
+            __syncthreads();
+            unsigned mask[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) mask[u] = 0xFu;
+            walk<Op, U, D, true, NT, true>(op, sched, n, skip_mix != 0, tile * kTileCols + 4 * lane, mask);
+            return;
+        }
+    }
+    if (tile >= ntiles) return;                 // from here on waves are independent: no block barrier
     int *tab = lds + wave * 2 * n;
     int *sched = tab + n;
 
-    constexpr int kTileCols = 256 * U;
     const int64_t c0 = tile * kTileCols;
     const int64_t c1 = (c0 + kTileCols < P) ? c0 + kTileCols : P;
     const int64_t off = c0 + 4 * lane;
@@ -327,7 +409,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
         if (b == c0 && e == c0 + kTileCols) {
 #pragma unroll
             for (int u = 0; u < U; ++u) mask[u] = 0xFu;
-            walk<Op, U, true, NT>(op, sched, n, skip_mix != 0, off, mask);
+            walk<Op, U, D, true, NT>(op, sched, n, skip_mix != 0, off, mask);
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -338,8 +420,119 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
                     if (c >= b && c < e) mask[u] |= 1u << q;
                 }
             }
-            walk<Op, U, false, NT>(op, sched, n, skip_mix != 0, off, mask);
+            walk<Op, U, D, false, NT>(op, sched, n, skip_mix != 0, off, mask);
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Out-of-place path: one short-lived workgroup per (gossiping row, column chunk).  It loads
+// the row's chunk and its partner's chunk, averages, and stores to the other buffer.  Each
+// chunk is fetched twice (once as "own", once as somebody's partner); the block order makes
+// the two fetches meet in one XCD's L2, so HBM still sees every element once:
+//   * workgroups go to the XCDs round-robin by block id, so block b belongs to XCD b % nxcd;
+//   * an XCD works through clusters of CL neighbouring chunks: all rows of the cluster's first
+//     chunk run, row after row, ... so a cluster's footprint (rows * CL * chunk bytes) lives
+//     in that XCD's L2 while both of its readers pass;
+//   * the XCDs hold neighbouring clusters at the same time, which keeps the stream of every
+//     row dense in DRAM.
+// Needs x_out != x_in (and v_out != v_in): a partner's input may be read after its owner
+// has stored.  Any table with entries in [0, n) is served, permutation or not.
+// ---------------------------------------------------------------------------------
+template <class Op, int U, bool NT>
+__global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
+    Op op, int n, int64_t P, int S, const int64_t *__restrict__ seg_off,
+    const int32_t *__restrict__ peers, int shift, int skip_mix, int64_t nchunks, int CL,
+    int xcd_shift)
+{
+    // grid: x = (chunk within cluster, xcd) with the xcd in the low bits, y = gossiping row,
+    // z = cluster.  Blocks are dispatched x-fastest, so an XCD sees, for one cluster, row 0's
+    // CL chunks, then row 1's, ... and no integer division is needed to decode the block.
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = uniform(threadIdx.x >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int xcd = blockIdx.x & ((1 << xcd_shift) - 1);
+    const int t = blockIdx.x >> xcd_shift;
+    const int row = blockIdx.y;
+    const int64_t chunk = ((static_cast<int64_t>(blockIdx.z) << xcd_shift) + xcd) * CL + t;
+    if (chunk >= nchunks) return;
+
+    constexpr int kTileCols = 256 * U;
+    const int64_t c0 = (chunk * nwaves + wave) * kTileCols;
+    if (c0 >= P) return;
+    const int64_t c1 = (c0 + kTileCols < P) ? c0 + kTileCols : P;
+    const int64_t off = c0 + 4 * lane;
+    const bool whole = c0 + kTileCols <= P;      // the tile does not hang over the row end
+
+    // The row's own data does not depend on the segment: put its loads in flight first and
+    // look the segment and the partner up while they travel.
+    typename Op::template Raw<U> mine;
+    unsigned full_mask[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) full_mask[u] = 0xFu;
+    if (whole) op.template issue<U, true, false>(row, off, full_mask, mine);
+
+    int lo = 1, hi = S;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (seg_off[mid] <= c0) lo = mid + 1; else hi = mid;
+    }
+    for (int s = lo - 1; s < S; ++s) {
+        int64_t sb = (s == 0) ? 0 : seg_off[s];
+        int64_t se = (s == S - 1) ? P : seg_off[s + 1];
+        sb = sb < 0 ? 0 : (sb > P ? P : sb);
+        se = se < 0 ? 0 : (se > P ? P : se);
+        if (sb >= c1) break;
+        if (sb < c0) sb = c0;
+        if (se > c1) se = c1;
+        if (sb >= se) continue;
+        int peer = row;
+        if (shift > 0) peer = row >= shift ? row - shift : row - shift + n;
+        else if (peers) peer = peers[static_cast<int64_t>(s) * n + row];
+        if (static_cast<unsigned>(peer) >= static_cast<unsigned>(n)) peer = row;
+
+        if (whole && sb == c0 && se == c0 + kTileCols) {
+            // fast path: one segment covers the tile; `mine` is already on its way
+            typename Op::template Raw<U> theirs;
+            if (!skip_mix) op.template issue<U, true, false>(peer, off, full_mask, theirs);
+            Tile<U> a, out;
+            op.template finish<U, true, NT, true>(row, off, full_mask, mine, a);
+            if (skip_mix) {
+                out = a;
+            } else {
+                Tile<U> c;
+                op.template finish<U, true, NT, false>(peer, off, full_mask, theirs, c);
+#pragma unroll
+                for (int u = 0; u < U; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
+            }
+            op.template store<U, true, NT>(row, off, full_mask, out);
+            return;
+        }
+        // boundary tile: per-element predication, once per overlapped segment
+        unsigned mask[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            mask[u] = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t c = off + u * 256 + q;
+                if (c >= sb && c < se) mask[u] |= 1u << q;
+            }
+        }
+        typename Op::template Raw<U> own, theirs;
+        op.template issue<U, false, false>(row, off, mask, own);
+        if (!skip_mix) op.template issue<U, false, false>(peer, off, mask, theirs);
+        Tile<U> a, out;
+        op.template finish<U, false, NT, true>(row, off, mask, own, a);
+        if (skip_mix) {
+            out = a;
+        } else {
+            Tile<U> c;
+            op.template finish<U, false, NT, false>(peer, off, mask, theirs, c);
+#pragma unroll
+            for (int u = 0; u < U; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
+        }
+        op.template store<U, false, NT>(row, off, mask, out);
     }
 }
 
@@ -377,10 +570,10 @@ __global__ __launch_bounds__(256) void copy_kernel(const float *src, float *dst,
 // Host side
 // ---------------------------------------------------------------------------------
 struct Launch {
-    int U, waves, nt;
+    int U, D, waves, nt, lockstep;
 };
 
-Launch pick_launch(int default_u)
+Launch pick_launch(int default_u, int default_d)
 {
     Launch l;
     l.U = cx_get_tuning(0);
@@ -389,6 +582,9 @@ Launch pick_launch(int default_u)
     if (l.waves < 1 || l.waves > kMaxWavesPerBlock) l.waves = 4;
     l.nt = cx_get_tuning(2);
     if (l.nt != 0 && l.nt != 1) l.nt = 1;
+    l.D = cx_get_tuning(3);
+    if (l.D != 2 && l.D != 4 && l.D != 8) l.D = default_d;
+    l.lockstep = cx_get_tuning(4) == 1 ? 1 : 0;
     return l;
 }
 
@@ -406,26 +602,119 @@ bool any_overlap(const void *a, const void *b, uint64_t bytes)
     return a == b || partial_overlap(a, b, bytes);
 }
 
-template <class Op>
-int launch_mix(const Op &op, int default_u, int n, int64_t P, int S, const int64_t *seg_off,
-               const int32_t *peers, int shift, int skip_mix, hipStream_t stream)
+struct MixArgs {
+    int n;
+    int64_t P;
+    int S;
+    const int64_t *seg_off;
+    const int32_t *peers;
+    int shift, skip_mix;
+    hipStream_t stream;
+    bool out_of_place;          // every output buffer is distinct from its input buffer
+    int rows_per_gossip_row;    // G: matrix rows behind one gossiping row (cluster footprint)
+};
+
+// A (slices, depth) pair is built for an operator only if its ring of in-flight rows stays
+// within the register file without spilling (at least two waves per SIMD stay resident).
+template <class Op, int U, int D>
+constexpr bool fits()
 {
-    const Launch l = pick_launch(default_u);
-    const int64_t tile_cols = 256 * l.U;
-    const int64_t ntiles = (P + tile_cols - 1) / tile_cols;
-    const int64_t nblocks = (ntiles + l.waves - 1) / l.waves;
-    if (nblocks > 0x7fffffffLL) return CX_ERR_SHAPE;
-    const dim3 grid(static_cast<unsigned>(nblocks)), block(kWave * l.waves);
-    const size_t lds = sizeof(int) * 2 * static_cast<size_t>(n) * l.waves;
-#define CX_LAUNCH(UU, NTT) \
-    hipLaunchKernelGGL((mix_kernel<Op, UU, NTT>), grid, block, lds, stream, op, n, P, S, seg_off, \
-                       peers, shift, skip_mix, ntiles)
-    if (l.nt) {
-        if (l.U == 1) CX_LAUNCH(1, true); else if (l.U == 2) CX_LAUNCH(2, true); else CX_LAUNCH(4, true);
+    return Op::kRawPerSlice * U * D * 4 <= 128 && !(U == 4 && Op::kRawPerSlice * D >= 8);
+}
+
+template <class Op, int U, int D>
+bool try_launch(const Op &op, const Launch &l, const MixArgs &a)
+{
+    if (l.U != U || l.D != D) return false;
+    if constexpr (!fits<Op, U, D>()) {
+        return false;
     } else {
-        if (l.U == 1) CX_LAUNCH(1, false); else if (l.U == 2) CX_LAUNCH(2, false); else CX_LAUNCH(4, false);
+        const int64_t tile_cols = 256 * U;
+        const int64_t ntiles = (a.P + tile_cols - 1) / tile_cols;
+        int waves = l.waves;
+        while (waves > 1 && sizeof(int) * 2 * static_cast<size_t>(a.n) * waves > 48 * 1024) --waves;
+        const int64_t nblocks = (ntiles + waves - 1) / waves;
+        const dim3 grid(static_cast<unsigned>(nblocks)), block(kWave * waves);
+        const size_t lds = sizeof(int) * 2 * static_cast<size_t>(a.n) * waves;
+        if (l.nt)
+            hipLaunchKernelGGL((mix_kernel<Op, U, D, true>), grid, block, lds, a.stream, op, a.n, a.P,
+                               a.S, a.seg_off, a.peers, a.shift, a.skip_mix, ntiles, l.lockstep);
+        else
+            hipLaunchKernelGGL((mix_kernel<Op, U, D, false>), grid, block, lds, a.stream, op, a.n, a.P,
+                               a.S, a.seg_off, a.peers, a.shift, a.skip_mix, ntiles, l.lockstep);
+        return true;
     }
-#undef CX_LAUNCH
+}
+
+// Out-of-place launch: one workgroup per (gossiping row, chunk of waves * 256 * U columns).
+template <class Op, int U>
+bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd_aware, const MixArgs &a,
+                int *status)
+{
+    if (want_u != U) return false;
+    const int64_t chunk_cols = static_cast<int64_t>(256) * U * waves;
+    const int64_t nchunks = (a.P + chunk_cols - 1) / chunk_cols;
+    const int nxcd = xcd_aware ? 8 : 1;
+    int64_t cl = cl_req;
+    if (cl < 1) {
+        // keep a cluster's footprint (all rows, CL chunks) at 4 MB, the size of one XCD's L2
+        // (measured optimum on MI355X: smaller loses DRAM row locality, larger loses L2 hits)
+        const int64_t row_bytes = chunk_cols * 4 * a.n * a.rows_per_gossip_row;
+        cl = (4 << 20) / row_bytes;
+        if (cl < 1) cl = 1;
+        if (cl > 64) cl = 64;
+    }
+    if (cl > 4096) cl = 4096;
+    int64_t clusters = (nchunks + cl * nxcd - 1) / (cl * nxcd);
+    if (clusters > 65535) {                       // grid.z limit: widen the clusters
+        cl = (nchunks + 65535LL * nxcd - 1) / (65535LL * nxcd);
+        clusters = (nchunks + cl * nxcd - 1) / (cl * nxcd);
+    }
+    if (cl * nxcd > 0x7fffffffLL || clusters > 65535 || a.n > 65535) { *status = CX_ERR_SHAPE; return true; }
+    const dim3 grid(static_cast<unsigned>(cl * nxcd), static_cast<unsigned>(a.n),
+                    static_cast<unsigned>(clusters));
+    const dim3 block(kWave * waves);
+    const int xcd_shift = xcd_aware ? 3 : 0;
+    if (nt)
+        hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, 0, a.stream, op, a.n, a.P, a.S,
+                           a.seg_off, a.peers, a.shift, a.skip_mix, nchunks, static_cast<int>(cl), xcd_shift);
+    else
+        hipLaunchKernelGGL((gather_kernel<Op, U, false>), grid, block, 0, a.stream, op, a.n, a.P, a.S,
+                           a.seg_off, a.peers, a.shift, a.skip_mix, nchunks, static_cast<int>(cl), xcd_shift);
+    *status = hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
+    return true;
+}
+
+template <class Op, int U0, int D0>
+int launch_mix(const Op &op, const MixArgs &a)
+{
+    static_assert(fits<Op, U0, D0>(), "default launch shape must fit");
+    if ((a.P + 255) / 256 > 0x7fffffffLL) return CX_ERR_SHAPE;
+    if (a.out_of_place && cx_get_tuning(5) != 1) {
+        int u = cx_get_tuning(0);
+        if (u != 1 && u != 2 && u != 4) u = 2;
+        while (Op::kRawPerSlice * u > 16) u >>= 1;     // two raw slots per lane must fit
+        int waves = cx_get_tuning(1);
+        if (waves < 1 || waves > kMaxWavesPerBlock) waves = 4;
+        const int nt = cx_get_tuning(2) == 0 ? 0 : 1;
+        const int cl = cx_get_tuning(6);
+        const int xcd_aware = cx_get_tuning(7) == 0 ? 0 : 1;
+        int status = CX_OK;
+        if (try_gather<Op, 1>(op, u, waves, nt, cl, xcd_aware, a, &status) ||
+            try_gather<Op, 2>(op, u, waves, nt, cl, xcd_aware, a, &status) ||
+            try_gather<Op, 4>(op, u, waves, nt, cl, xcd_aware, a, &status))
+            return status;
+    }
+    Launch l = pick_launch(U0, D0);
+    const bool done =
+        try_launch<Op, 1, 2>(op, l, a) || try_launch<Op, 1, 4>(op, l, a) || try_launch<Op, 1, 8>(op, l, a) ||
+        try_launch<Op, 2, 2>(op, l, a) || try_launch<Op, 2, 4>(op, l, a) || try_launch<Op, 2, 8>(op, l, a) ||
+        try_launch<Op, 4, 2>(op, l, a) || try_launch<Op, 4, 4>(op, l, a) || try_launch<Op, 4, 8>(op, l, a);
+    if (!done) {                     // requested shape not built for this operator
+        l.U = U0;
+        l.D = D0;
+        try_launch<Op, U0, D0>(op, l, a);
+    }
     return hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
 }
 
@@ -454,7 +743,8 @@ int cx_gossip_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_
     const int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
     if (rc != CX_OK) return rc;
     const MeanOp<1> op{x_in, x_out, ld, 1.0f};
-    return launch_mix(op, 4, W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream));
+    const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream), x_in != x_out, 1};
+    return launch_mix<MeanOp<1>, 4, 2>(op, a);
 }
 
 int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P, int32_t G,
@@ -472,12 +762,13 @@ int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t 
     const float inv_g = 1.0f / static_cast<float>(G);
     const int skip = (L == 1) ? 1 : 0;
     const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
+    const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
     switch (G) {
-    case 1: return launch_mix(MeanOp<1>{x_in, x_out, ld, inv_g}, 4, L, P, S, seg_off_dev, peers, 0, skip, st);
-    case 2: return launch_mix(MeanOp<2>{x_in, x_out, ld, inv_g}, 4, L, P, S, seg_off_dev, peers, 0, skip, st);
-    case 4: return launch_mix(MeanOp<4>{x_in, x_out, ld, inv_g}, 2, L, P, S, seg_off_dev, peers, 0, skip, st);
-    case 8: return launch_mix(MeanOp<8>{x_in, x_out, ld, inv_g}, 2, L, P, S, seg_off_dev, peers, 0, skip, st);
-    case 16: return launch_mix(MeanOp<16>{x_in, x_out, ld, inv_g}, 1, L, P, S, seg_off_dev, peers, 0, skip, st);
+    case 1: return launch_mix<MeanOp<1>, 2, 4>(MeanOp<1>{x_in, x_out, ld, inv_g}, a);
+    case 2: return launch_mix<MeanOp<2>, 2, 4>(MeanOp<2>{x_in, x_out, ld, inv_g}, a);
+    case 4: return launch_mix<MeanOp<4>, 1, 4>(MeanOp<4>{x_in, x_out, ld, inv_g}, a);
+    case 8: return launch_mix<MeanOp<8>, 1, 4>(MeanOp<8>{x_in, x_out, ld, inv_g}, a);
+    case 16: return launch_mix<MeanOp<16>, 1, 2>(MeanOp<16>{x_in, x_out, ld, inv_g}, a);
     default: return CX_ERR_UNSUPPORTED;
     }
 }
@@ -500,7 +791,8 @@ int cx_pushsum_mix(const float *x_in, float *x_out, const float *w_in, float *w_
     hipLaunchKernelGGL(pushsum_weight_kernel, dim3(1), dim3(256), 0, st, w_in, w_out, W, hop);
     if (hipGetLastError() != hipSuccess) return CX_ERR_HIP;
     const PushOp op{x_in, x_out, z_out, w_in, ld, W, hop};
-    return launch_mix(op, 4, W, P, 1, /*seg_off: unused for S == 1*/ nullptr, nullptr, hop, 0, st);
+    const MixArgs a{W, P, 1, /*seg_off: unused for S == 1*/ nullptr, nullptr, hop, 0, st, x_in != x_out, 1};
+    return launch_mix<PushOp, 2, 4>(op, a);
 }
 
 int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *v_out,
@@ -521,7 +813,9 @@ int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *
         any_overlap(g, x_out, bytes) || any_overlap(g, v_out, bytes))
         return CX_ERR_ALIAS;
     const FusedOp op{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd};
-    return launch_mix(op, 2, W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream));
+    const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream),
+                    x_in != x_out && v_in != v_out, 1};
+    return launch_mix<FusedOp, 1, 4>(op, a);
 }
 
 int cx_copy_baseline(const float *src, float *dst, int64_t n, void *stream)
@@ -530,7 +824,7 @@ int cx_copy_baseline(const float *src, float *dst, int64_t n, void *stream)
     if (n < 4 || (n & 3) != 0) return CX_ERR_SHAPE;
     if (misaligned(src) || misaligned(dst)) return CX_ERR_ALIGN;
     if (any_overlap(src, dst, static_cast<uint64_t>(n) * 4u)) return CX_ERR_ALIAS;
-    const Launch l = pick_launch(4);
+    const Launch l = pick_launch(1, 2);
     const int64_t nslices = n / 4;
     const int64_t ntiles = (nslices + 64 * l.U - 1) / (64 * l.U);
     const int64_t nblocks = (ntiles + 3) / 4;

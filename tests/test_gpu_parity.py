@@ -51,10 +51,14 @@ def test_gossip_bit_exact_under_every_launch_shape(tuning):
         want = O.gossip_mix(want, P, so, tabs[r])
     with Tuning(*tuning):
         xd, sod = dev(x), dev(so)
+        y0, y1 = dev(x), dev(x)
         for r in range(3):
             cx.cx_gossip_mix(xd, xd, P, sod, dev(tabs[r]))
+            cx.cx_gossip_mix(y0, y1, P, sod, dev(tabs[r]))
+            y0, y1 = y1, y0
         torch.cuda.synchronize()
     assert same_bits(host(xd), want)
+    assert same_bits(host(y0), want)
 
 
 def test_gossip_edge_values_signed_zero_subnormal_overflow():
@@ -77,7 +81,7 @@ def test_gossip_ragged_and_degenerate_segments():
     S = len(so) - 1
     pe = O.topology(3, W, S, 0, 1)[0]
     want = O.gossip_mix(x, P, so, pe)
-    for tuning in [(-1, -1, -1), (1, 2, 1)]:
+    for tuning in [(-1, -1, -1, -1), (1, 2, 1, 2), (4, 1, 0, 4), (2, 8, 1, 8)]:
         with Tuning(*tuning):
             assert same_bits(run_gossip(x, P, so, pe, True), want)
     # one segment per column
@@ -96,18 +100,27 @@ def test_gossip_max_rows():
     assert same_bits(run_gossip(x, P, so, pe, True), O.gossip_mix(x, P, so, pe))
 
 
-def test_table_that_is_not_a_permutation_means_no_mixing_for_that_segment():
+def test_tables_that_are_not_permutations():
     W, P = 4, 2000
     x = WL.gen_matrix(W, P, 1.0, seed=24)
     so = np.array([0, 700, 1400, 2000], dtype=np.int64)
     good = O.topology(24, W, 3, 0, 1)[0]
     bad = good.copy()
-    bad[1] = [1, 1, 2, 3]          # duplicate
+    bad[1] = [1, 1, 2, 3]          # duplicate (and a fixed point)
     bad[2] = [1, 2, 3, 9]          # out of range
+    # in place the rows of a segment are walked cycle by cycle, which needs a permutation:
+    # a segment whose table is not one is left unmixed (identity table)
     ref = bad.copy()
     ref[1] = ref[2] = np.arange(W)
     assert same_bits(run_gossip(x, P, so, bad, True), O.gossip_mix(x, P, so, ref))
+    # out of place every row averages with whatever row the table names (an "unfair" table
+    # with duplicates is served as written); an index outside [0, W) means the row itself
+    ref = bad.copy()
+    ref[2] = [1, 2, 3, 3]
     assert same_bits(run_gossip(x, P, so, bad, False), O.gossip_mix(x, P, so, ref))
+    with Tuning(force_walk=1):
+        ref[1] = ref[2] = np.arange(W)
+        assert same_bits(run_gossip(x, P, so, bad, False), O.gossip_mix(x, P, so, ref))
 
 
 def test_deterministic_and_inplace_equals_pingpong_over_rounds():
@@ -177,10 +190,14 @@ def test_hier_rounds_under_every_launch_shape(tuning):
         want = O.hier_mix_f32(want, P, G, so, tabs[r])
     with Tuning(*tuning):
         xd = dev(x)
+        y0, y1 = dev(x), dev(x)
         for r in range(R):
             cx.cx_hier_mix(xd, xd, P, G, dev(so), dev(tabs[r]))
+            cx.cx_hier_mix(y0, y1, P, G, dev(so), dev(tabs[r]))
+            y0, y1 = y1, y0
         torch.cuda.synchronize()
     assert same_bits(host(xd), want)
+    assert same_bits(host(y0), want)
 
 
 # --------------------------------------------------------------------------- fused SGD
