@@ -3,7 +3,8 @@
 
 A step is one gossip round over the whole workload: generate the round's peer tables
 (Algorithm 2, host), upload them (a few KB), and run one mixing launch over all W rows
-(Algorithm 1) in place.  The parameter matrix is resident in HBM before timing starts.
+(Algorithm 1) from one HBM-resident buffer into the other (ping-pong; --in-place updates a
+single buffer instead).  The parameter matrix is resident in HBM before timing starts.
 Prints ONE JSON line (see the design doc for the fields).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--all]
@@ -38,7 +39,7 @@ def describe(wl) -> str:
 class Runner:
     """Holds one workload's device state and issues its steps."""
 
-    def __init__(self, wl, kind, total_rounds):
+    def __init__(self, wl, kind, total_rounds, in_place=False):
         import torch
         from paper_2012_15198_amd import cxmix as cx
         from paper_2012_15198_amd import workloads as WL
@@ -47,7 +48,12 @@ class Runner:
         self.so_host = WL.seg_off_for(wl)
         cx.cx_check_segments(self.so_host, wl.P)
         self.so = torch.from_numpy(self.so_host).to(dev)
-        self.x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, device=dev)
+        # layout: rows padded to a multiple of 1024 floats (4 KB) so every row starts on a cache
+        # line and DRAM page boundary; two buffers, the rounds ping-pong between them
+        self.in_place = in_place
+        self.ld = (wl.P + 1023) // 1024 * 1024
+        self.x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=self.ld, device=dev)
+        self.y = self.x if in_place else torch.empty_like(self.x)
         self.n = wl.L if kind == "hier" else wl.W
         self.S = 1 if kind == "pushsum" else wl.S
         self.mode = 1 if kind == "pushsum" else 0
@@ -58,7 +64,8 @@ class Runner:
         self.bytes_per_elem = 8
         if kind == "fused":
             self.v = torch.zeros_like(self.x)
-            self.g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, stream=2, device=dev)
+            self.v2 = self.v if in_place else torch.empty_like(self.v)
+            self.g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
             self.bytes_per_elem = 20
         if kind == "pushsum":
             self.w = [torch.ones(wl.W, device=dev), torch.zeros(wl.W, device=dev)]
@@ -75,15 +82,17 @@ class Runner:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
         if self.kind == "gossip":
-            cx.cx_gossip_mix(self.x, self.x, wl.P, self.so, tab)
+            cx.cx_gossip_mix(self.x, self.y, wl.P, self.so, tab)
         elif self.kind == "hier":
-            cx.cx_hier_mix(self.x, self.x, wl.P, wl.G, self.so, tab)
+            cx.cx_hier_mix(self.x, self.y, wl.P, wl.G, self.so, tab)
         elif self.kind == "fused":
-            cx.cx_sgd_fused_mix(self.x, self.x, self.v, self.v, self.g, wl.lr, wl.mu, wl.wd, wl.P,
+            cx.cx_sgd_fused_mix(self.x, self.y, self.v, self.v2, self.g, wl.lr, wl.mu, wl.wd, wl.P,
                                 self.so, tab)
+            self.v, self.v2 = self.v2, self.v
         elif self.kind == "pushsum":
             hop = int((0 - int(self.tab_np[r, 0, 0])) % wl.W)
-            cx.cx_pushsum_mix(self.x, self.x, self.w[r & 1], self.w[1 - (r & 1)], None, wl.P, hop)
+            cx.cx_pushsum_mix(self.x, self.y, self.w[r & 1], self.w[1 - (r & 1)], None, wl.P, hop)
+        self.x, self.y = self.y, self.x
         if timed:
             e1.record()
             self.ev.append((e0, e1))
@@ -114,6 +123,19 @@ class Runner:
             "kernel_GBps": alg_bytes / (k_avg * 1e-3) / 1e9,
             "alg_bytes_per_launch": alg_bytes,
         }
+
+
+def measured_traffic(workload, kind, in_place):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE, scaled by the copy-kernel calibration), or None if there is none for this case."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_{kind}_{'inplace' if in_place else 'pingpong'}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def copy_ceiling(nbytes, reps=10):
@@ -168,6 +190,8 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads' entry points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy", action="store_true")
+    ap.add_argument("--in-place", action="store_true",
+                    help="update the matrix in place (cycle-walk kernel) instead of ping-pong buffers")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (W simulated workers share one MI355X); "
@@ -181,7 +205,7 @@ def main():
 
     wl = WL.WORKLOADS[args.workload]
     kind = {"gossip": "gossip", "hier": "hier", "fused+pushsum": "fused"}[wl.kind]
-    runner = Runner(wl, kind, args.steps + args.warmup)
+    runner = Runner(wl, kind, args.steps + args.warmup, in_place=args.in_place)
     res = runner.run(args.steps, args.warmup)
     out = {
         "metric": "gossip-mix HBM GB/s and params-mixed/s per round (fraction of HBM peak), 1 GPU",
@@ -189,13 +213,16 @@ def main():
         "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(wl), "entry_point": f"cx_{kind}_mix" if kind != "fused" else "cx_sgd_fused_mix",
-                   "rounds_timed": args.steps, "in_place": True,
+                   "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
+                   "buffers": "in place" if args.in_place else "ping-pong (x_in -> x_out, swapped every round)",
                    "step": "cx_topology_gen(1 round) + table upload + one mixing launch"},
         "params_mixed_per_s": res["params_mixed_per_s"],
         "frac_of_hbm_peak": res["GBps"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": res["kernel_GBps"], "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": res["kernel_GBps"] / HBM_PEAK_GBPS, "traffic": None,
-                     "kernel": "mix_kernel", "kernel_ms_avg": res["kernel_ms_avg"],
+                     "unit": "GB/s", "frac": res["kernel_GBps"] / HBM_PEAK_GBPS,
+                     "traffic": measured_traffic(wl.name, kind, args.in_place),
+                     "kernel": "mix_kernel" if args.in_place else "gather_kernel",
+                     "kernel_ms_avg": res["kernel_ms_avg"],
                      "kernel_ms_min": res["kernel_ms_min"], "kernel_ms_median": res["kernel_ms_median"],
                      "alg_bytes_per_launch": res["alg_bytes_per_launch"]},
     }
@@ -215,7 +242,7 @@ def main():
         for name, k, steps in plan:
             if name == args.workload and k == kind:
                 continue
-            r = Runner(WL.WORKLOADS[name], k, steps + 3)
+            r = Runner(WL.WORKLOADS[name], k, steps + 3, in_place=args.in_place)
             rr = r.run(steps, 3)
             rr["workload"] = describe(WL.WORKLOADS[name])
             rr["frac_of_hbm_peak_kernel"] = rr["kernel_GBps"] / HBM_PEAK_GBPS

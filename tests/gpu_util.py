@@ -47,3 +47,19 @@ ALL_TUNINGS = [(-1, -1, -1, -1), (1, 1, 0, 2), (2, 2, 1, 4), (4, 8, 0, 2), (1, 4
                # out-of-place launches: (slices, waves, nt, -, -, force_walk, cluster, xcd_aware)
                (1, 4, 1, -1, -1, 0, 1, 0), (2, 2, 0, -1, -1, 0, 7, 1), (4, 8, 1, -1, -1, 0, 64, 1),
                (4, 1, 1, 2, 0, 1, -1, -1), (2, 4, 1, 4, 1, 1, -1, -1)]
+
+
+def fused_scales(x, v, g, lr, mu, wd, seg_off, peers):
+    """Magnitudes the 1e-6 relative bound of the fused step is taken against.  The fp32 path
+    rounds six times on the way to x' (wd*x, +g, mu*v, +, lr*v', x-); each rounding is
+    relative to an intermediate no larger than M = |x| + lr*(mu*|v| + |g| + wd*|x|), so the
+    error of x' is a few 2^-24 of max(M_own, M_partner), however small x' itself is.  For v'
+    the same holds with N = mu*|v| + |g| + wd*|x|."""
+    x, v, g = (np.abs(a.astype(np.float64)) for a in (x, v, g))
+    n = mu * v + g + wd * x
+    m = x + lr * n
+    mp = m.copy()
+    for s in range(len(seg_off) - 1):
+        c0, c1 = seg_off[s], seg_off[s + 1]
+        mp[:, c0:c1] = np.maximum(m[:, c0:c1], m[peers[s], c0:c1])
+    return mp, n

@@ -1,0 +1,199 @@
+"""Full-size parity on the five benchmark workloads, in the launch configuration bench.py
+times (rows padded to 1024 floats, ping-pong buffers, default launch parameters) and in place.
+
+Mixing is independent per column, so at sizes the oracle cannot sweep in seconds the check
+runs on a column sample -- everything within 64 columns of a segment boundary, the first and
+last 4096 columns and 20,000 seeded random columns -- for ALL rows and ALL rounds: the sample
+is cut out of the device matrix before the first round, the oracle advances it round by
+round with the same peer tables, and the device result is cut out again at the end.
+C1 and C2 are also compared element by element on the whole matrix."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2012_15198_amd import cxmix as cx
+from paper_2012_15198_amd import workloads as WL
+from gpu_util import Tuning, bits, dev, fused_scales, host, same_bits
+
+pytestmark = pytest.mark.gpu
+REL = 1e-6
+
+
+def padded(P):
+    return (P + 1023) // 1024 * 1024
+
+
+def take(x, cols_dev):
+    return host(x.index_select(1, cols_dev))
+
+
+def sample(wl, so):
+    cols = WL.sample_columns(wl.P, so, wl.seed)
+    return cols, WL.sub_seg_off(cols, so), dev(cols)
+
+
+def free(*tensors):
+    del tensors
+    torch.cuda.empty_cache()
+
+
+def test_c1_all_rounds_whole_matrix():
+    wl = WL.WORKLOADS["C1"]
+    so = WL.equal_seg_off(wl.P, wl.S)
+    x = WL.gen_matrix(wl.W, wl.P, wl.sigma, wl.seed, ld=padded(wl.P))
+    tabs = cx.cx_topology_gen(wl.seed, wl.W, wl.S, 0, wl.rounds)
+    assert (tabs == O.topology(wl.seed, wl.W, wl.S, 0, wl.rounds)).all()
+    want = x
+    for r in range(wl.rounds):
+        want = O.gossip_mix(want, wl.P, so, tabs[r])
+    sod = dev(so)
+    a, b, c = dev(x), dev(x), dev(x)
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        cx.cx_gossip_mix(a, b, wl.P, sod, t)
+        a, b = b, a
+        cx.cx_gossip_mix(c, c, wl.P, sod, t)
+    torch.cuda.synchronize()
+    assert same_bits(host(a), want) and same_bits(host(c), want)
+
+
+def test_c2_whole_matrix_three_rounds_and_sampled_all_rounds():
+    wl = WL.WORKLOADS["C2"]
+    so = WL.equal_seg_off(wl.P, wl.S)
+    ld = padded(wl.P)
+    tabs = cx.cx_topology_gen(wl.seed, wl.W, wl.S, 0, wl.rounds)
+    assert (tabs == O.topology(wl.seed, wl.W, wl.S, 0, wl.rounds)).all()
+    xd = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld)
+    cols, sso, cold = sample(wl, so)
+    sub = take(xd, cold)
+    x0 = host(xd)
+    a, b = xd, torch.empty_like(xd)
+    c = xd.clone()
+    sod = dev(so)
+    want = x0
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        cx.cx_gossip_mix(a, b, wl.P, sod, t)
+        a, b = b, a
+        cx.cx_gossip_mix(c, c, wl.P, sod, t)
+        sub = O.gossip_mix(sub, len(cols), sso, tabs[r])
+        if r < 3:
+            out = np.empty_like(want)
+            out[:, wl.P:] = want[:, wl.P:]
+            want = O.gossip_mix(want, wl.P, so, tabs[r], out=out)
+            if r == 2:
+                torch.cuda.synchronize()
+                assert same_bits(host(a)[:, :wl.P], want[:, :wl.P])
+                assert same_bits(host(c)[:, :wl.P], want[:, :wl.P])
+    torch.cuda.synchronize()
+    assert same_bits(take(a, cold), sub) and same_bits(take(c, cold), sub)
+    # invariant at any size: the column means survive all rounds
+    m0 = x0[:, :wl.P:997].astype(np.float64).mean(0)
+    m1 = host(a[:, :wl.P:997]).astype(np.float64).mean(0)
+    assert np.abs(m1 - m0).max() <= wl.rounds * 2.0 ** -24 * np.abs(x0).max()
+    free(a, b, c, xd)
+
+
+def hier_bound(xsub, G, ysub64, pe, sso):
+    W, n = xsub.shape
+    L = W // G
+    a = np.abs(xsub.astype(np.float64)).reshape(L, G, n).mean(1)
+    scale = a.copy()
+    for s in range(len(sso) - 1):
+        c0, c1 = sso[s], sso[s + 1]
+        scale[:, c0:c1] = 0.5 * (a[:, c0:c1] + a[pe[s], c0:c1])
+    return REL * np.maximum(np.abs(ysub64), np.repeat(scale, G, axis=0))
+
+
+@pytest.mark.parametrize("name", ["C3", "C5"])
+def test_hierarchical_workloads_sampled_all_rounds(name):
+    wl = WL.WORKLOADS[name]
+    so = WL.seg_off_for(wl)
+    cx.cx_check_segments(so, wl.P)
+    ld = padded(wl.P)
+    tabs = cx.cx_topology_gen(wl.seed, wl.L, wl.S, 0, wl.rounds)
+    assert (tabs == O.topology(wl.seed, wl.L, wl.S, 0, wl.rounds)).all()
+    xd = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld)
+    cols, sso, cold = sample(wl, so)
+    sub = take(xd, cold)
+    a, b = xd, torch.empty_like(xd)
+    sod = dev(so)
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        before = take(a, cold)
+        if r % 2 == 0:                       # alternate the two code paths over the rounds
+            cx.cx_hier_mix(a, b, wl.P, wl.G, sod, t)
+            a, b = b, a
+        else:
+            cx.cx_hier_mix(a, a, wl.P, wl.G, sod, t)
+        after = take(a, cold)
+        # every round: one step of the fp64 reference from the device's own input
+        y64 = O.hier_mix_f64(before, len(cols), wl.G, sso, tabs[r])
+        assert (np.abs(after - y64) <= hier_bound(before, wl.G, y64, tabs[r], sso)).all(), r
+        sub = O.hier_mix_f32(sub, len(cols), wl.G, sso, tabs[r])
+        assert same_bits(after, sub), r      # and the fixed-order fp32 trajectory, bit for bit
+    grouped = after.reshape(wl.L, wl.G, -1)
+    assert (grouped == grouped[:, :1]).all()
+    free(a, b, xd)
+
+
+def test_c4_fused_sgd_sampled_all_rounds():
+    wl = WL.WORKLOADS["C4"]
+    so = WL.equal_seg_off(wl.P, wl.S)
+    ld = padded(wl.P)
+    tabs = cx.cx_topology_gen(wl.seed, wl.W, wl.S, 0, wl.rounds)
+    x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld)
+    g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, ld=ld, stream=2)
+    v = torch.zeros_like(x)
+    x2, v2 = torch.empty_like(x), torch.empty_like(x)
+    cols, sso, cold = sample(wl, so)
+    sx, sv, sg = take(x, cold), take(v, cold), take(g, cold)
+    sod = dev(so)
+    n = len(cols)
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        bx, bv = take(x, cold), take(v, cold)
+        if r % 2 == 0:
+            cx.cx_sgd_fused_mix(x, x2, v, v2, g, wl.lr, wl.mu, wl.wd, wl.P, sod, t)
+            x, x2, v, v2 = x2, x, v2, v
+        else:
+            cx.cx_sgd_fused_mix(x, x, v, v, g, wl.lr, wl.mu, wl.wd, wl.P, sod, t)
+        ax, av = take(x, cold), take(v, cold)
+        x64, v64 = O.sgd_fused_mix_f64(bx, bv, sg, wl.lr, wl.mu, wl.wd, n, sso, tabs[r])
+        xs, vs = fused_scales(bx, bv, sg, wl.lr, wl.mu, wl.wd, sso, tabs[r])
+        assert (np.abs(ax - x64) <= REL * np.maximum(np.abs(x64), xs)).all(), r
+        assert (np.abs(av - v64) <= REL * np.maximum(np.abs(v64), vs)).all(), r
+        sx, sv = O.sgd_fused_mix_f32(sx, sv, sg, wl.lr, wl.mu, wl.wd, n, sso, tabs[r])
+        assert same_bits(ax, sx) and same_bits(av, sv), r
+    free(x, x2, v, v2, g)
+
+
+def test_c4_pushsum_sampled_all_rounds():
+    wl = WL.WORKLOADS["C4"]
+    ld = padded(wl.P)
+    shifts = cx.cx_topology_gen(wl.seed, wl.W, 1, 0, wl.rounds, 1)
+    assert (shifts == O.topology(wl.seed, wl.W, 1, 0, wl.rounds, 1)).all()
+    x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld)
+    x2 = torch.empty_like(x)
+    z = torch.empty_like(x)
+    cols, _, cold = sample(wl, np.array([0, wl.P]))
+    sx = take(x, cold)
+    mean = sx.astype(np.float64).mean(0)
+    sw = np.ones(wl.W, dtype=np.float32)
+    w0, w1 = torch.ones(wl.W, device=x.device), torch.zeros(wl.W, device=x.device)
+    for r in range(wl.rounds):
+        hop = int((0 - int(shifts[r, 0, 0])) % wl.W)
+        assert hop == 2 ** (r % 7)
+        if r % 2 == 0:
+            cx.cx_pushsum_mix(x, x2, w0, w1, z, wl.P, hop)
+            x, x2 = x2, x
+        else:
+            cx.cx_pushsum_mix(x, x, w0, w1, z, wl.P, hop)
+        w0, w1 = w1, w0
+        sx, sw, sz = O.pushsum_mix_f32(sx, sw, len(cols), hop, True)
+        assert same_bits(take(x, cold), sx) and same_bits(take(z, cold), sz), r
+        assert (host(w0) == 1.0).all()
+        if r == 6:      # after log2(W) = 7 exponential hops every row holds the exact mean
+            assert np.abs(take(x, cold) - mean).max() <= 1e-6 * np.abs(mean).max() + 1e-7
+    free(x, x2, z)

@@ -10,7 +10,7 @@ import torch
 import oracle as O
 from paper_2012_15198_amd import cxmix as cx
 from paper_2012_15198_amd import workloads as WL
-from gpu_util import ALL_TUNINGS, Tuning, bits, dev, host, same_bits
+from gpu_util import ALL_TUNINGS, Tuning, bits, dev, fused_scales, host, same_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -217,13 +217,9 @@ def test_fused_matches_fp64_reference_and_fixed_order_fp32(W, P, ld, S, inplace)
     torch.cuda.synchronize()
     gx, gv = host(xo), host(vo)
     x64, v64 = O.sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, so, pe)
-    ax = np.abs(x[:, :P].astype(np.float64))
-    xscale = ax.copy()
-    for s in range(S):
-        xscale[:, so[s]:so[s + 1]] = np.maximum(ax[:, so[s]:so[s + 1]], ax[pe[s], so[s]:so[s + 1]])
-    assert (np.abs(gx[:, :P] - x64[:, :P]) <= REL * np.maximum(np.abs(x64[:, :P]), xscale)).all()
-    vscale = np.maximum(np.abs(v[:, :P]), np.abs(g[:, :P])).astype(np.float64)
-    assert (np.abs(gv[:, :P] - v64[:, :P]) <= REL * np.maximum(np.abs(v64[:, :P]), vscale)).all()
+    xs, vs = fused_scales(x[:, :P], v[:, :P], g[:, :P], lr, mu, wd, so, pe)
+    assert (np.abs(gx[:, :P] - x64[:, :P]) <= REL * np.maximum(np.abs(x64[:, :P]), xs)).all()
+    assert (np.abs(gv[:, :P] - v64[:, :P]) <= REL * np.maximum(np.abs(v64[:, :P]), vs)).all()
     x32, v32 = O.sgd_fused_mix_f32(x, v, g, lr, mu, wd, P, so, pe)
     assert same_bits(gx, x32) and same_bits(gv, v32)
     assert same_bits(host(gd), g)
