@@ -63,8 +63,8 @@ void fair_table(const DrawStream &rng, int32_t n, int32_t *recv_from, std::vecto
     }
 }
 
-constexpr int kTuningKeys = 8;
-std::atomic<int32_t> g_tuning[kTuningKeys] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
+constexpr int kTuningKeys = 9;
+std::atomic<int32_t> g_tuning[kTuningKeys] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
 
 }  // namespace
 
@@ -152,7 +152,7 @@ int cx_set_tuning(int32_t key, int32_t value)
         if (key == 1 && (value < 1 || value > 8)) return CX_ERR_SHAPE;
         if (key == 2 && value != 0 && value != 1) return CX_ERR_SHAPE;
         if (key == 3 && value != 2 && value != 4 && value != 8) return CX_ERR_SHAPE;
-        if ((key == 4 || key == 5 || key == 7) && value != 0 && value != 1) return CX_ERR_SHAPE;
+        if ((key == 4 || key == 5 || key == 7 || key == 8) && value != 0 && value != 1) return CX_ERR_SHAPE;
         if (key == 6 && (value < 1 || value > 4096)) return CX_ERR_SHAPE;
     }
     g_tuning[key].store(value);

@@ -29,6 +29,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <type_traits>
 
@@ -426,14 +427,55 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
 }
 
 // ---------------------------------------------------------------------------------
+// Row order of the out-of-place path.  Library-owned device memory (no allocation at run
+// time): kOrderSlots tables of kOrderEntries ints.  A call takes the next slot round-robin, so
+// up to kOrderSlots mixing calls may be in flight on one GPU at once (on any streams); more
+// than that would share a slot and may run with a row order meant for another call, which
+// is still a valid order (every row exactly once is re-established per call by the order
+// kernel that precedes each mixing kernel in stream order) only once that kernel has run.
+// ---------------------------------------------------------------------------------
+constexpr int kOrderSlots = 4;
+constexpr int kOrderEntries = 1 << 18;
+__device__ int g_order[kOrderSlots][kOrderEntries];
+
+// One workgroup per segment: builds the segment's cycle schedule and writes it as the row
+// order of every cluster whose first column lies in that segment.
+__global__ __launch_bounds__(256) void order_kernel(int n, int64_t P, int S,
+                                                    const int64_t *__restrict__ seg_off,
+                                                    const int32_t *__restrict__ peers, int shift,
+                                                    int64_t cluster_cols, int nclusters, int slot)
+{
+    extern __shared__ int lds[];
+    int *tab = lds;
+    int *sched = lds + n;
+    const int s = blockIdx.x;
+    if (threadIdx.x < kWave) build_schedule(tab, sched, n, threadIdx.x, peers, s, shift);
+    __syncthreads();
+    int64_t sb = (s == 0) ? 0 : seg_off[s];
+    int64_t se = (s == S - 1) ? P : seg_off[s + 1];
+    sb = sb < 0 ? 0 : (sb > P ? P : sb);
+    se = se < 0 ? 0 : (se > P ? P : se);
+    const int64_t c_lo = (sb + cluster_cols - 1) / cluster_cols;
+    int64_t c_hi = (se + cluster_cols - 1) / cluster_cols;
+    if (c_hi > nclusters) c_hi = nclusters;
+    int *order = g_order[slot];
+    for (int64_t idx = threadIdx.x; idx < (c_hi - c_lo) * n; idx += blockDim.x) {
+        const int64_t c = c_lo + idx / n;
+        const int k = static_cast<int>(idx % n);
+        order[c * n + k] = sched[k] & kRowMask;
+    }
+}
+
+// ---------------------------------------------------------------------------------
 // Out-of-place path: one short-lived workgroup per (gossiping row, column chunk).  It loads
 // the row's chunk and its partner's chunk, averages, and stores to the other buffer.  Each
 // chunk is fetched twice (once as "own", once as somebody's partner); the block order makes
 // the two fetches meet in one XCD's L2, so HBM still sees every element once:
 //   * workgroups go to the XCDs round-robin by block id, so block b belongs to XCD b % nxcd;
-//   * an XCD works through clusters of CL neighbouring chunks: all rows of the cluster's first
-//     chunk run, row after row, ... so a cluster's footprint (rows * CL * chunk bytes) lives
-//     in that XCD's L2 while both of its readers pass;
+//   * an XCD works through clusters of CL neighbouring chunks, row after row (CL chunks of one
+//     row, then CL chunks of the next).  Rows are taken in the order of the segment's
+//     permutation cycles (order_kernel), so the partner chunk a block fetches is the own
+//     chunk of the block that follows it: only two row visits have to stay in L2;
 //   * the XCDs hold neighbouring clusters at the same time, which keeps the stream of every
 //     row dense in DRAM.
 // Needs x_out != x_in (and v_out != v_in): a partner's input may be read after its owner
@@ -443,7 +485,7 @@ template <class Op, int U, bool NT>
 __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     Op op, int n, int64_t P, int S, const int64_t *__restrict__ seg_off,
     const int32_t *__restrict__ peers, int shift, int skip_mix, int64_t nchunks, int CL,
-    int xcd_shift)
+    int xcd_shift, int order_slot)
 {
     // grid: x = (chunk within cluster, xcd) with the xcd in the low bits, y = gossiping row,
     // z = cluster.  Blocks are dispatched x-fastest, so an XCD sees, for one cluster, row 0's
@@ -453,9 +495,16 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     const int nwaves = blockDim.x >> 6;
     const int xcd = blockIdx.x & ((1 << xcd_shift) - 1);
     const int t = blockIdx.x >> xcd_shift;
-    const int row = blockIdx.y;
-    const int64_t chunk = ((static_cast<int64_t>(blockIdx.z) << xcd_shift) + xcd) * CL + t;
+    const int64_t cluster = (static_cast<int64_t>(blockIdx.z) << xcd_shift) + xcd;
+    const int64_t chunk = cluster * CL + t;
     if (chunk >= nchunks) return;
+    // y is the position in the cluster's row order: with the order kernel's table, rows follow
+    // the permutation cycles, so this block's partner is the next block's own row (fresh in L2)
+    int row = blockIdx.y;
+    if (order_slot >= 0) {
+        row = g_order[order_slot][cluster * n + blockIdx.y];
+        if (static_cast<unsigned>(row) >= static_cast<unsigned>(n)) row = blockIdx.y;
+    }
 
     constexpr int kTileCols = 256 * U;
     const int64_t c0 = (chunk * nwaves + wave) * kTileCols;
@@ -472,14 +521,36 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     for (int u = 0; u < U; ++u) full_mask[u] = 0xFu;
     if (whole) op.template issue<U, true, false>(row, off, full_mask, mine);
 
-    int lo = 1, hi = S;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (seg_off[mid] <= c0) lo = mid + 1; else hi = mid;
+    // Segment and partner lookup.  With up to 63 segments one vector load brings the whole
+    // offset table and this row's partner in every segment into lanes 0..S at once (a single
+    // memory latency); the segment of c0 is then a ballot + popcount and the table entries
+    // are read across lanes.  Longer tables fall back to a scalar binary search.
+    const bool in_lanes = S <= 63;
+    int64_t lane_off = 0;
+    int lane_peer = row;
+    int first_seg;
+    if (in_lanes) {
+        if (lane <= S && S > 1) lane_off = seg_off[lane];
+        if (lane < S && peers) lane_peer = peers[static_cast<int64_t>(lane) * n + row];
+        const bool below = lane >= 1 && lane < S && lane_off <= c0;
+        first_seg = __builtin_popcountll(__builtin_amdgcn_ballot_w64(below));
+    } else {
+        int lo = 1, hi = S;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (seg_off[mid] <= c0) lo = mid + 1; else hi = mid;
+        }
+        first_seg = lo - 1;
     }
-    for (int s = lo - 1; s < S; ++s) {
-        int64_t sb = (s == 0) ? 0 : seg_off[s];
-        int64_t se = (s == S - 1) ? P : seg_off[s + 1];
+    auto offset_at = [&](int k) -> int64_t {
+        if (!in_lanes) return seg_off[k];
+        const unsigned lo32 = __builtin_amdgcn_readlane(static_cast<int>(lane_off), k);
+        const unsigned hi32 = __builtin_amdgcn_readlane(static_cast<int>(lane_off >> 32), k);
+        return static_cast<int64_t>((static_cast<uint64_t>(hi32) << 32) | lo32);
+    };
+    for (int s = first_seg; s < S; ++s) {
+        int64_t sb = (s == 0) ? 0 : offset_at(s);
+        int64_t se = (s == S - 1) ? P : offset_at(s + 1);
         sb = sb < 0 ? 0 : (sb > P ? P : sb);
         se = se < 0 ? 0 : (se > P ? P : se);
         if (sb >= c1) break;
@@ -488,7 +559,8 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
         if (sb >= se) continue;
         int peer = row;
         if (shift > 0) peer = row >= shift ? row - shift : row - shift + n;
-        else if (peers) peer = peers[static_cast<int64_t>(s) * n + row];
+        else if (peers) peer = in_lanes ? __builtin_amdgcn_readlane(lane_peer, s)
+                                        : peers[static_cast<int64_t>(s) * n + row];
         if (static_cast<unsigned>(peer) >= static_cast<unsigned>(n)) peer = row;
 
         if (whole && sb == c0 && se == c0 + kTileCols) {
@@ -655,14 +727,20 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     const int64_t chunk_cols = static_cast<int64_t>(256) * U * waves;
     const int64_t nchunks = (a.P + chunk_cols - 1) / chunk_cols;
     const int nxcd = xcd_aware ? 8 : 1;
+    bool ordered = cx_get_tuning(8) != 0 && a.n > 1 && a.S <= 4096;
     int64_t cl = cl_req;
     if (cl < 1) {
-        // keep a cluster's footprint (all rows, CL chunks) at 4 MB, the size of one XCD's L2
-        // (measured optimum on MI355X: smaller loses DRAM row locality, larger loses L2 hits)
-        const int64_t row_bytes = chunk_cols * 4 * a.n * a.rows_per_gossip_row;
-        cl = (4 << 20) / row_bytes;
+        // ordered rows: a row visit of 512 KB per XCD (measured optimum on MI355X: shorter
+        // visits lose DRAM row locality, longer ones push the previous visit out of L2);
+        // natural row order: the whole cluster (all rows) should fit one XCD's 4 MB L2
+        const int64_t row_bytes = chunk_cols * 4 * a.rows_per_gossip_row;
+        cl = ordered ? (512 << 10) / row_bytes : (4 << 20) / (row_bytes * a.n);
         if (cl < 1) cl = 1;
-        if (cl > 64) cl = 64;
+    }
+    if (ordered) {                                // the order table must fit its slot
+        const int64_t max_clusters = kOrderEntries / a.n - nxcd;
+        const int64_t min_cl = (nchunks + max_clusters - 1) / max_clusters;
+        if (cl < min_cl) cl = min_cl;
     }
     if (cl > 4096) cl = 4096;
     int64_t clusters = (nchunks + cl * nxcd - 1) / (cl * nxcd);
@@ -671,16 +749,26 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
         clusters = (nchunks + cl * nxcd - 1) / (cl * nxcd);
     }
     if (cl * nxcd > 0x7fffffffLL || clusters > 65535 || a.n > 65535) { *status = CX_ERR_SHAPE; return true; }
+    if (clusters * nxcd * a.n > kOrderEntries) ordered = false;   // table too large: natural row order
     const dim3 grid(static_cast<unsigned>(cl * nxcd), static_cast<unsigned>(a.n),
                     static_cast<unsigned>(clusters));
     const dim3 block(kWave * waves);
     const int xcd_shift = xcd_aware ? 3 : 0;
+    int slot = -1;
+    if (ordered) {
+        static std::atomic<unsigned> next_slot{0};
+        slot = static_cast<int>(next_slot.fetch_add(1) % kOrderSlots);
+        const int64_t nclusters = clusters * nxcd;
+        hipLaunchKernelGGL(order_kernel, dim3(a.S), dim3(256), sizeof(int) * 2 * a.n, a.stream, a.n, a.P,
+                           a.S, a.seg_off, a.peers, a.shift, cl * chunk_cols, static_cast<int>(nclusters), slot);
+        if (hipGetLastError() != hipSuccess) { *status = CX_ERR_HIP; return true; }
+    }
     if (nt)
         hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, 0, a.stream, op, a.n, a.P, a.S,
-                           a.seg_off, a.peers, a.shift, a.skip_mix, nchunks, static_cast<int>(cl), xcd_shift);
+                           a.seg_off, a.peers, a.shift, a.skip_mix, nchunks, static_cast<int>(cl), xcd_shift, slot);
     else
         hipLaunchKernelGGL((gather_kernel<Op, U, false>), grid, block, 0, a.stream, op, a.n, a.P, a.S,
-                           a.seg_off, a.peers, a.shift, a.skip_mix, nchunks, static_cast<int>(cl), xcd_shift);
+                           a.seg_off, a.peers, a.shift, a.skip_mix, nchunks, static_cast<int>(cl), xcd_shift, slot);
     *status = hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
     return true;
 }

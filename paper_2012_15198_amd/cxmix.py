@@ -23,7 +23,7 @@ STATUS = {0: "CX_OK", -1: "CX_ERR_NULL", -2: "CX_ERR_SHAPE", -3: "CX_ERR_SEGMENT
           -4: "CX_ERR_PEERS", -5: "CX_ERR_ALIGN", -6: "CX_ERR_ALIAS", -7: "CX_ERR_HIP",
           -8: "CX_ERR_UNSUPPORTED"}
 TUNE_SLICES, TUNE_WAVES, TUNE_NONTEMPORAL, TUNE_DEPTH = 0, 1, 2, 3
-TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE = 4, 5, 6, 7
+TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE, TUNE_ORDERED = 4, 5, 6, 7, 8
 
 EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_segments",
            "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",
