@@ -22,19 +22,36 @@
  *   stream     a hipStream_t passed as void* (NULL = the default stream).  Mixing
  *              calls only enqueue work: they never synchronise, never allocate and
  *              never free device memory.  The caller owns every buffer and must keep
- *              it alive until the stream has passed the call.
- *   in place   x_out may be the same pointer as x_in (each element is then read
- *              once and written once); otherwise the two matrices must not overlap
- *              (CX_ERR_ALIAS).  All values are computed from the round's input rows
- *              (Algorithm 1 posts every send before any averaging).
+ *              it alive until the stream has passed the call.  A call enqueues one
+ *              mixing kernel (out of place: preceded by a few-microsecond kernel that
+ *              derives the row order from the peer table).
+ *   buffers    x_out may be the same pointer as x_in (in place) or a second matrix that
+ *              does not overlap it (out of place, e.g. two buffers used in turn round
+ *              after round); partial overlap is CX_ERR_ALIAS.  Either way every value is
+ *              computed from the round's input rows (Algorithm 1 posts every send before
+ *              any averaging), every element is read from HBM once and written once, and
+ *              the results are bit-identical.  The two cases run different kernels:
+ *              in place, one wavefront owns a column tile and walks the rows along the
+ *              cycles of the peer permutation; out of place, one short workgroup per
+ *              (row, column chunk) reads the row and its peer and writes the result --
+ *              the faster of the two on MI355X (about 74 % against about 66 % of the HBM
+ *              peak on a 32 x 25.6M matrix).
+ *   peer table in place, each peers[s] must be a permutation of 0..n-1: a segment whose
+ *              table is not one is left unmixed (treated as the identity).  Out of place,
+ *              any table with entries in [0, n) is served as written (a table with
+ *              duplicates, i.e. a random topology without fair peer selection, included);
+ *              an entry outside [0, n) stands for the row itself.  Segment offsets are
+ *              clamped to [0, P].  No table content can make a kernel index out of bounds.
+ *              Device tables are NOT read by the host: check their host mirrors with
+ *              cx_check_segments / cx_check_peers before uploading.
+ *   scratch    the out-of-place kernels keep a row-order table in library-owned device
+ *              memory (static, 8 slots of 1 MiB per GPU), so no call allocates.  A slot is
+ *              bound to the stream that first uses it; calls on one stream run in order, so
+ *              a table is never rewritten while it is read.  Calls on a ninth and later
+ *              stream run without the table: same results, lower speed.
  *   limits     at most CX_MAX_ROWS gossiping rows (W, or W/G in hierarchical mode).
- *   return     CX_OK (0) or a negative cx_status.  Argument errors are detected on
- *              the host before anything is enqueued.  Device tables are NOT read by
- *              the host: check their host mirrors with cx_check_segments /
- *              cx_check_peers before uploading.  The kernels never index out of
- *              bounds on a bad table: segment offsets are clamped to [0,P] and a
- *              peers[s] that is not a permutation of 0..n-1 is replaced, for that
- *              segment, by the identity (every row pairs with itself: no mixing).
+ *   return     CX_OK (0) or a negative cx_status.  Argument errors are detected on the host
+ *              before anything is enqueued.
  */
 #ifndef CX_MIX_H
 #define CX_MIX_H
@@ -151,9 +168,13 @@ int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *
  * cx_copy_baseline: dst[i] = src[i] for n floats (n % 4 == 0, 16-byte aligned) with the
  * same load/store instructions as the mixing kernels; the practical HBM ceiling and the
  * calibration kernel for the profiler's byte counters.
- * cx_set_tuning / cx_get_tuning: process-global launch parameters for sweeps.
- *   key 0: 16-byte slices per lane per row (1, 2, 4)      key 1: waves per workgroup (1..8) 
- *   key 2: non-temporal loads/stores (0/1)                key 3: rows in flight per lane (2, 4, 8)
+ * cx_set_tuning / cx_get_tuning: process-global launch parameters for sweeps and tests.
+ *   key 0: 16-byte slices per lane per row (1, 2, 4)      key 1: waves per workgroup (1..8)
+ *   key 2: non-temporal stores (and in-place loads) (0/1) key 3: in place: rows in flight per lane (2, 4, 8)
+ *   key 4: in place: workgroup walks rows in lock-step (0/1)
+ *   key 5: 1 = use the in-place kernel for out-of-place calls too
+ *   key 6: out of place: chunks per cluster (1..4096)     key 7: out of place: XCD-aware block order (0/1)
+ *   key 8: out of place: rows ordered along the permutation cycles (0/1)
  * A (key 0, key 3) pair that an operator was not built with falls back to its default.
  * cx_set_tuning returns CX_ERR_SHAPE for an unknown key or value; a value of -1 restores
  * the default.

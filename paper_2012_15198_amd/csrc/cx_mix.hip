@@ -1,36 +1,45 @@
-// Device half of the gossip-mixing library for gfx950 (MI355X): the column-owner
-// mixing kernels behind cx_gossip_mix / cx_hier_mix / cx_pushsum_mix /
-// cx_sgd_fused_mix, and their C-ABI launchers.
+// Device half of the gossip-mixing library for gfx950 (MI355X): the mixing kernels behind
+// cx_gossip_mix / cx_hier_mix / cx_pushsum_mix / cx_sgd_fused_mix and their C-ABI launchers.
 //
-// Design (one kernel, one HBM pass per round):
-//  * Mixing is independent per column, so one lane OWNS a 16-byte column slice
-//    (4 consecutive fp32 columns) -- U slices per lane, 1 KB contiguous per wave per
-//    row access -- and visits every row of that slice.  A wavefront owns a tile of
-//    256*U columns; wavefronts never talk to each other (no barriers, no atomics on
-//    global memory).
-//  * The per-segment peer table is a permutation, so the rows of a column split into
-//    cycles i -> peers[i] -> peers[peers[i]] ...  Walking a cycle, the lane holds the
-//    current and the next row's slice in registers, writes (cur + next) * 0.5f to the
-//    current row and moves on; the cycle's first slice is kept for its last row.
-//    Every element is therefore read once and written once (8 B per worker-parameter),
-//    and the update may run in place: a row is overwritten only after its two readers
-//    (itself and the one row that receives from it) have it in registers.
-//  * The cycle order of a segment is built per wavefront in LDS (wave-private, a few
-//    hundred bytes) from the device-resident peer table; a table that is not a
-//    permutation is replaced by the identity, so no row index can leave [0, n).
-//  * Tiles that lie wholly inside one segment take the 16-byte vector path; the at most
-//    S+1 tiles that straddle a segment boundary or the ragged end of the row take the
-//    same walk once per overlapped segment with per-element predication.
-//  * Hierarchical mode loads the G rows of a group and reduces them in registers with a
-//    fixed pairwise tree before the walk over group leaders; the result is stored to all
-//    G rows.  The fused mode applies the momentum-SGD update as each row is loaded.
-//    Push-sum is the walk over the shift permutation, plus the scalar weights.
+// Mixing is independent per column and every element has to be read once and written once
+// (8 B per worker-parameter; 20 B with the fused optimizer), so the whole path is bound by
+// HBM bandwidth.  A lane always handles 16-byte column slices (4 fp32), a wavefront 1 KB of
+// contiguous columns per memory instruction.  Two kernels serve the same arithmetic:
+//
+//  gather_kernel (output buffer != input buffer) -- the fast one.
+//   * One short-lived workgroup per (gossiping row, column chunk): it loads the row's chunk
+//     and its partner's chunk, averages, stores to the other buffer.  Every chunk is
+//     fetched twice from L2 but once from HBM: blocks are ordered so that both fetches meet
+//     in the L2 of one XCD (block b runs on XCD b mod 8; an XCD walks a cluster of
+//     neighbouring chunks row after row; rows follow the cycles of the peer permutation,
+//     so a block's partner is the next block's own row).
+//   * Long contiguous row visits per XCD keep the DRAM row buffers busy, which a kernel
+//     whose waves each wander over all rows cannot do (measured: 74 % vs 66 % of peak).
+//   * order_kernel, a few microseconds ahead of it, derives the row order from the
+//     device-resident peer table into library-owned device memory (no allocation).
+//
+//  mix_kernel (in place capable) -- the column-owner cycle walk.
+//   * A wavefront owns a tile of 256*U columns and visits every row of it.  The peer table
+//     of a segment is a permutation, so the rows split into cycles i -> peers[i] -> ...
+//     Walking a cycle, the lane keeps the current and the next row's slice in registers,
+//     writes (cur + next) * 0.5f to the current row and moves on; the cycle's first slice
+//     is kept for its last row.  A row is overwritten only after its two readers have it
+//     in registers, so x_out may be x_in.  Loads run D rows ahead of the stores.
+//   * The cycle order of a segment is built per wavefront (or once per workgroup in the
+//     lock-step variant) in LDS from the peer table; a table that is not a permutation is
+//     replaced by the identity, so no row index can leave [0, n).
+//
+//  Both: tiles wholly inside one segment take the 16-byte vector path; the at most S+1
+//  tiles that straddle a segment boundary or the ragged row end run once per overlapped
+//  segment with per-element predication.  Row operators (MeanOp / FusedOp / PushOp) say
+//  what loading and storing a "gossiping row" means: the pairwise-tree mean of a group of
+//  G rows, the momentum-SGD update applied on the way in, or the push-sum de-biasing.
 #include "cx_mix.h"
 
 #include <hip/hip_runtime.h>
 
-#include <atomic>
 #include <cstdint>
+#include <mutex>
 #include <type_traits>
 
 #pragma clang fp contract(off)
@@ -428,13 +437,12 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
 
 // ---------------------------------------------------------------------------------
 // Row order of the out-of-place path.  Library-owned device memory (no allocation at run
-// time): kOrderSlots tables of kOrderEntries ints.  A call takes the next slot round-robin, so
-// up to kOrderSlots mixing calls may be in flight on one GPU at once (on any streams); more
-// than that would share a slot and may run with a row order meant for another call, which
-// is still a valid order (every row exactly once is re-established per call by the order
-// kernel that precedes each mixing kernel in stream order) only once that kernel has run.
+// time): kOrderSlots tables of kOrderEntries ints per GPU.  A slot belongs to ONE stream
+// (first come, first served, for the life of the process): calls on a stream run in stream
+// order, so a slot is never rewritten while an earlier call still reads it.  Streams beyond
+// the first kOrderSlots run without a table (natural row order: same results, slower).
 // ---------------------------------------------------------------------------------
-constexpr int kOrderSlots = 4;
+constexpr int kOrderSlots = 8;
 constexpr int kOrderEntries = 1 << 18;
 __device__ int g_order[kOrderSlots][kOrderEntries];
 
@@ -563,21 +571,36 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
                                         : peers[static_cast<int64_t>(s) * n + row];
         if (static_cast<unsigned>(peer) >= static_cast<unsigned>(n)) peer = row;
 
-        if (whole && sb == c0 && se == c0 + kTileCols) {
-            // fast path: one segment covers the tile; `mine` is already on its way
-            typename Op::template Raw<U> theirs;
-            if (!skip_mix) op.template issue<U, true, false>(peer, off, full_mask, theirs);
+        // `mine` holds (or will hold) this row's data; average it with the partner's and store.
+        // Operators with many rows behind a gossiping row (hierarchical groups) reduce their
+        // own rows before the partner's are requested, which halves the registers in flight.
+        auto mix_and_store = [&](auto full_c, const unsigned (&m)[U]) {
+            constexpr bool FULL = decltype(full_c)::value;
+            constexpr bool kOneAtATime = Op::kRawPerSlice * U >= 16;
             Tile<U> a, out;
-            op.template finish<U, true, NT, true>(row, off, full_mask, mine, a);
             if (skip_mix) {
+                op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
                 out = a;
             } else {
                 Tile<U> c;
-                op.template finish<U, true, NT, false>(peer, off, full_mask, theirs, c);
+                if constexpr (kOneAtATime) {
+                    op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
+                    op.template issue<U, FULL, false>(peer, off, m, mine);
+                    op.template finish<U, FULL, NT, false>(peer, off, m, mine, c);
+                } else {
+                    typename Op::template Raw<U> theirs;
+                    op.template issue<U, FULL, false>(peer, off, m, theirs);
+                    op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
+                    op.template finish<U, FULL, NT, false>(peer, off, m, theirs, c);
+                }
 #pragma unroll
                 for (int u = 0; u < U; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
             }
-            op.template store<U, true, NT>(row, off, full_mask, out);
+            op.template store<U, FULL, NT>(row, off, m, out);
+        };
+        if (whole && sb == c0 && se == c0 + kTileCols) {
+            // fast path: one segment covers the tile; `mine` is already on its way
+            mix_and_store(std::true_type{}, full_mask);
             return;
         }
         // boundary tile: per-element predication, once per overlapped segment
@@ -591,20 +614,8 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
                 if (c >= sb && c < se) mask[u] |= 1u << q;
             }
         }
-        typename Op::template Raw<U> own, theirs;
-        op.template issue<U, false, false>(row, off, mask, own);
-        if (!skip_mix) op.template issue<U, false, false>(peer, off, mask, theirs);
-        Tile<U> a, out;
-        op.template finish<U, false, NT, true>(row, off, mask, own, a);
-        if (skip_mix) {
-            out = a;
-        } else {
-            Tile<U> c;
-            op.template finish<U, false, NT, false>(peer, off, mask, theirs, c);
-#pragma unroll
-            for (int u = 0; u < U; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
-        }
-        op.template store<U, false, NT>(row, off, mask, out);
+        op.template issue<U, false, false>(row, off, mask, mine);
+        mix_and_store(std::false_type{}, mask);
     }
 }
 
@@ -718,6 +729,20 @@ bool try_launch(const Op &op, const Launch &l, const MixArgs &a)
     }
 }
 
+// Order-table slot owned by `stream`, or -1 if all slots belong to other streams.
+int order_slot_for(hipStream_t stream)
+{
+    static std::mutex mu;
+    static hipStream_t owner[kOrderSlots];
+    static int used = 0;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i)
+        if (owner[i] == stream) return i;
+    if (used == kOrderSlots) return -1;
+    owner[used] = stream;
+    return used++;
+}
+
 // Out-of-place launch: one workgroup per (gossiping row, chunk of waves * 256 * U columns).
 template <class Op, int U>
 bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd_aware, const MixArgs &a,
@@ -728,6 +753,8 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     const int64_t nchunks = (a.P + chunk_cols - 1) / chunk_cols;
     const int nxcd = xcd_aware ? 8 : 1;
     bool ordered = cx_get_tuning(8) != 0 && a.n > 1 && a.S <= 4096;
+    int slot = ordered ? order_slot_for(a.stream) : -1;
+    if (slot < 0) ordered = false;
     int64_t cl = cl_req;
     if (cl < 1) {
         // ordered rows: a row visit of 512 KB per XCD (measured optimum on MI355X: shorter
@@ -754,10 +781,8 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
                     static_cast<unsigned>(clusters));
     const dim3 block(kWave * waves);
     const int xcd_shift = xcd_aware ? 3 : 0;
-    int slot = -1;
+    if (!ordered) slot = -1;
     if (ordered) {
-        static std::atomic<unsigned> next_slot{0};
-        slot = static_cast<int>(next_slot.fetch_add(1) % kOrderSlots);
         const int64_t nclusters = clusters * nxcd;
         hipLaunchKernelGGL(order_kernel, dim3(a.S), dim3(256), sizeof(int) * 2 * a.n, a.stream, a.n, a.P,
                            a.S, a.seg_off, a.peers, a.shift, cl * chunk_cols, static_cast<int>(nclusters), slot);
@@ -781,7 +806,8 @@ int launch_mix(const Op &op, const MixArgs &a)
     if (a.out_of_place && cx_get_tuning(5) != 1) {
         int u = cx_get_tuning(0);
         if (u != 1 && u != 2 && u != 4) u = 2;
-        while (Op::kRawPerSlice * u > 16) u >>= 1;     // two raw slots per lane must fit
+        while (u > 1 && Op::kRawPerSlice * u > 8) u >>= 1;   // the rows in flight must fit the registers
+        if (Op::kRawPerSlice >= 8) u = 1;
         int waves = cx_get_tuning(1);
         if (waves < 1 || waves > kMaxWavesPerBlock) waves = 4;
         const int nt = cx_get_tuning(2) == 0 ? 0 : 1;

@@ -144,6 +144,26 @@ def test_deterministic_and_inplace_equals_pingpong_over_rounds():
     assert torch.equal(a.view(torch.int32), c.view(torch.int32))
 
 
+def test_out_of_place_calls_on_more_streams_than_order_table_slots():
+    W, P, S = 16, 40003, 4
+    x = WL.gen_matrix(W, P, 1.0, seed=26, ld=40960)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(26, W, S, 0, 12)
+    sod = dev(so)
+    streams = [torch.cuda.Stream() for _ in range(12)]
+    ins = [dev(x) for _ in streams]
+    outs = [torch.empty_like(a) for a in ins]
+    tds = [dev(t) for t in tabs]
+    torch.cuda.synchronize()
+    for rep in range(2):            # second pass: every stream meets its slot (or none) again
+        for st, a, b, t in zip(streams, ins, outs, tds):
+            with torch.cuda.stream(st):
+                cx.cx_gossip_mix(a, b, P, sod, t, stream=st)
+    torch.cuda.synchronize()
+    for b, t in zip(outs, tabs):
+        assert same_bits(host(b)[:, :P], O.gossip_mix(x, P, so, t)[:, :P])
+
+
 # ------------------------------------------------------------------------ hierarchical
 def hier_tol(x, G, P, y64, pe, so):
     """1e-6 relative to max(|ref|, mean |x| over the rows that enter the result)."""
