@@ -187,6 +187,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C2")
+    ap.add_argument("--kind", default=None, choices=[None, "gossip", "hier", "fused", "pushsum"],
+                    help="entry point to time (default: the workload's own; C4 has fused and pushsum)")
     ap.add_argument("--all", action="store_true", help="also time the other workloads' entry points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy", action="store_true")
@@ -204,7 +206,7 @@ def main():
     cx.lib()                                            # fail loudly if the library is not built
 
     wl = WL.WORKLOADS[args.workload]
-    kind = {"gossip": "gossip", "hier": "hier", "fused+pushsum": "fused"}[wl.kind]
+    kind = args.kind or {"gossip": "gossip", "hier": "hier", "fused+pushsum": "fused"}[wl.kind]
     runner = Runner(wl, kind, args.steps + args.warmup, in_place=args.in_place)
     res = runner.run(args.steps, args.warmup)
     out = {
@@ -212,7 +214,8 @@ def main():
         "value": res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": describe(wl), "entry_point": f"cx_{kind}_mix" if kind != "fused" else "cx_sgd_fused_mix",
+        "config": {"workload": describe(wl) if kind != "gossip" or wl.G == 1 else describe(wl) + " (flat gossip over all rows)",
+                   "entry_point": f"cx_{kind}_mix" if kind != "fused" else "cx_sgd_fused_mix",
                    "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
                    "buffers": "in place" if args.in_place else "ping-pong (x_in -> x_out, swapped every round)",
                    "step": "cx_topology_gen(1 round) + table upload + one mixing launch"},
