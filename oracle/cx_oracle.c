@@ -23,7 +23,9 @@
  * double-stochasticity on every table; W=2 / W=3 hand cases; column-mean
  * conservation; the halving of the deviation norm at W=3; G=W equals the plain
  * column mean; log2(W) exponential hops equal the exact mean; the fused update
- * with mixing off equals torch.optim.SGD.  No function here is "parity unpinned".
+ * with mixing off equals torch.optim.SGD; the gradient-reducing hierarchical step
+ * with one group equals SGD on the averaged gradient.  No function here is
+ * "parity unpinned".
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -277,6 +279,86 @@ int oracle_sgd_fused_mix_f32(const float *x_in, const float *v_in, const float *
                 x_out[i * ld + c] = (xh[i] + xh[peers[(int64_t)s * W + i]]) * 0.5f;
         }
     free(xh);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Hierarchical Crossover-SGD as Section 3.3 states it: (1) the gradients of  */
+/* the G workers of a group are reduced (averaged) at the group's leader,     */
+/* which applies them to its model with the momentum-SGD step above; (2) the  */
+/* L = W/G leaders gossip segment-wise on the updated parameters; (3) every   */
+/* leader's result is broadcast to its group.                                 */
+/*   x  float [W][ld]  only leader rows (row g*G) are read; all rows written  */
+/*   v  float [L][ld]  the leaders' momentum                                  */
+/*   g  float [W][ld]  every worker's gradient                                */
+/* With L == 1 step (2) is empty: this is AllReduce-SGD.                      */
+/* ------------------------------------------------------------------------- */
+int oracle_hier_sgd_fused_mix_f64(const float *x_in, const float *v_in, const float *g,
+                                  double *x_out, double *v_out, float lr, float mu, float wd,
+                                  int64_t ld, int32_t W, int64_t P, int32_t G, int32_t S,
+                                  const int64_t *seg_off, const int32_t *leader_peers)
+{
+    (void)P;
+    int32_t L = W / G;
+    double *h = (double *)malloc(sizeof(double) * (size_t)L);
+    if (!h) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t q = 0; q < L; ++q) {
+                double gbar = 0.0;
+                for (int32_t j = 0; j < G; ++j)
+                    gbar += (double)g[((int64_t)q * G + j) * ld + c];
+                gbar /= (double)G;
+                double xl = (double)x_in[(int64_t)q * G * ld + c];
+                double gp = gbar + (double)wd * xl;
+                double vn = (double)mu * (double)v_in[(int64_t)q * ld + c] + gp;
+                v_out[(int64_t)q * ld + c] = vn;
+                h[q] = xl - (double)lr * vn;
+            }
+            for (int32_t q = 0; q < L; ++q) {
+                double y = h[q];
+                if (L > 1) y = (h[q] + h[leader_peers[(int64_t)s * L + q]]) * 0.5;
+                for (int32_t j = 0; j < G; ++j)
+                    x_out[((int64_t)q * G + j) * ld + c] = y;
+            }
+        }
+    free(h);
+    return 0;
+}
+
+/* Same steps in fp32 with the fixed order: pairwise-tree gradient sum times the
+ * fp32 reciprocal of G, then the unfused fp32 optimizer step and average. */
+int oracle_hier_sgd_fused_mix_f32(const float *x_in, const float *v_in, const float *g,
+                                  float *x_out, float *v_out, float lr, float mu, float wd,
+                                  int64_t ld, int32_t W, int64_t P, int32_t G, int32_t S,
+                                  const int64_t *seg_off, const int32_t *leader_peers)
+{
+    (void)P;
+    int32_t L = W / G;
+    float inv_g = 1.0f / (float)G;
+    float *h = (float *)malloc(sizeof(float) * (size_t)L);
+    if (!h) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t q = 0; q < L; ++q) {
+                float gbar = tree_sum_f32(g + (int64_t)q * G * ld + c, ld, G) * inv_g;
+                float xl = x_in[(int64_t)q * G * ld + c];
+                float t0 = wd * xl;
+                float gp = gbar + t0;
+                float t1 = mu * v_in[(int64_t)q * ld + c];
+                float vn = t1 + gp;
+                float t2 = lr * vn;
+                v_out[(int64_t)q * ld + c] = vn;
+                h[q] = xl - t2;
+            }
+            for (int32_t q = 0; q < L; ++q) {
+                float y = h[q];
+                if (L > 1) y = (h[q] + h[leader_peers[(int64_t)s * L + q]]) * 0.5f;
+                for (int32_t j = 0; j < G; ++j)
+                    x_out[((int64_t)q * G + j) * ld + c] = y;
+            }
+        }
+    free(h);
     return 0;
 }
 

@@ -21,7 +21,8 @@ _lib = None
 
 __all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topology",
            "gossip_mix", "hier_mix_f64", "hier_mix_f32", "sgd_fused_mix_f64",
-           "sgd_fused_mix_f32", "pushsum_mix_f64", "pushsum_mix_f32"]
+           "sgd_fused_mix_f32", "pushsum_mix_f64", "pushsum_mix_f32",
+           "hier_sgd_fused_mix_f64", "hier_sgd_fused_mix_f32"]
 
 
 def build_oracle(force: bool = False) -> str:
@@ -56,6 +57,8 @@ def _L():
                                                  i64, i32, i64, i32, vp, vp]
         lib.oracle_sgd_fused_mix_f32.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32,
                                                  i64, i32, i64, i32, vp, vp]
+        for fn in (lib.oracle_hier_sgd_fused_mix_f64, lib.oracle_hier_sgd_fused_mix_f32):
+            fn.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_pushsum_mix_f64.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
         lib.oracle_pushsum_mix_f32.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
         _lib = lib
@@ -203,3 +206,31 @@ def pushsum_mix_f64(x, w, P, hop, want_z=True):
 
 def pushsum_mix_f32(x, w, P, hop, want_z=True):
     return _push(_L().oracle_pushsum_mix_f32, np.float32, x, w, P, hop, want_z)
+
+
+def _hier_fused(fn, odtype, x, v, g, lr, mu, wd, P, G, seg_off, leader_peers):
+    x, v, g = _mat(x), _mat(v), _mat(g)
+    W, ld = x.shape
+    if G < 1 or W % G:
+        raise ValueError("G must divide W")
+    L = W // G
+    if g.shape != x.shape or v.shape != (L, ld):
+        raise ValueError("g must be [W][ld] and v [W/G][ld]")
+    so = _seg(seg_off, P)
+    S = len(so) - 1
+    pe = _peers(leader_peers, S, L) if L > 1 else None
+    xo, vo = x.astype(odtype), v.astype(odtype)
+    _check(fn(_p(x), _p(v), _p(g), _p(xo), _p(vo), lr, mu, wd, ld, W, P, G, S, _p(so), _p(pe)),
+           "hier_sgd_fused_mix")
+    return xo, vo
+
+
+def hier_sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, G, seg_off, leader_peers):
+    """Section 3.3 with gradients: x [W][ld] (leader rows read), v [W/G][ld], g [W][ld]."""
+    return _hier_fused(_L().oracle_hier_sgd_fused_mix_f64, np.float64, x, v, g, lr, mu, wd, P, G,
+                       seg_off, leader_peers)
+
+
+def hier_sgd_fused_mix_f32(x, v, g, lr, mu, wd, P, G, seg_off, leader_peers):
+    return _hier_fused(_L().oracle_hier_sgd_fused_mix_f32, np.float32, x, v, g, lr, mu, wd, P, G,
+                       seg_off, leader_peers)

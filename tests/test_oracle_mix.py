@@ -294,3 +294,84 @@ def test_log2w_exponential_hops_give_the_exact_mean(W):
     assert np.abs(xf - mean).max() < 1e-6
     assert np.abs(x64 - mean).max() < 1e-6
     assert abs(wf.sum() - W) == 0
+
+
+# ------------------------------------------- hierarchical step with gradients (Section 3.3)
+def test_hier_sgd_hand_case():
+    # W=4, G=2, leaders 0 and 2 swap.  Leader x: 2 and 6 (member rows hold junk that must
+    # not be read).  Gradients: group 0 mean (1+3)/2 = 2, group 1 mean (5+7)/2 = 6.
+    # mu=0.5, v = 4 and 8; wd=0.5: g' = 2 + 1 = 3, 6 + 3 = 9; v' = 2 + 3 = 5, 4 + 9 = 13
+    # lr=0.5: h = 2 - 2.5 = -0.5, 6 - 6.5 = -0.5 -> everyone ends at -0.5
+    x = f32([[2.0], [99.0], [6.0], [-77.0]])
+    v = f32([[4.0], [8.0]])
+    g = f32([[1.0], [3.0], [5.0], [7.0]])
+    xo, vo = O.hier_sgd_fused_mix_f64(x, v, g, 0.5, 0.5, 0.5, 1, 2, [0, 1], [[1, 0]])
+    assert xo[:, 0].tolist() == [-0.5] * 4 and vo[:, 0].tolist() == [5.0, 13.0]
+    x32, v32 = O.hier_sgd_fused_mix_f32(x, v, g, 0.5, 0.5, 0.5, 1, 2, [0, 1], [[1, 0]])
+    assert x32.tolist() == xo.tolist() and v32.tolist() == vo.tolist()
+    # three groups, table [1,2,0], lr chosen so h = x - v' differs per group
+    x = f32([[1.0], [0.0], [2.0], [0.0], [4.0], [0.0]])
+    g = f32([[1.0], [1.0], [2.0], [4.0], [8.0], [0.0]])       # means 1, 3, 4
+    v = np.zeros((3, 1), dtype=np.float32)
+    xo, vo = O.hier_sgd_fused_mix_f64(x, v, g, 1.0, 0.0, 0.0, 1, 2, [0, 1], [[1, 2, 0]])
+    # h = 0, -1, 0 ; y0 = (0 + -1)/2, y1 = (-1 + 0)/2, y2 = (0 + 0)/2
+    assert xo[:, 0].tolist() == [-0.5, -0.5, -0.5, -0.5, 0.0, 0.0] and vo[:, 0].tolist() == [1.0, 3.0, 4.0]
+
+
+def test_hier_sgd_g1_is_the_flat_fused_step():
+    W, P, S = 6, 50, 3
+    x = WL.gen_matrix(W, P, 0.05, 20)
+    v = WL.gen_matrix(W, P, 0.01, 20, stream=1)
+    g = WL.gen_matrix(W, P, 0.01, 20, stream=2)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(20, W, S, 0, 1)[0]
+    a = O.hier_sgd_fused_mix_f32(x, v, g, 0.1, 0.9, 1e-4, P, 1, so, pe)
+    b = O.sgd_fused_mix_f32(x, v, g, 0.1, 0.9, 1e-4, P, so, pe)
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all()
+    a = O.hier_sgd_fused_mix_f64(x, v, g, 0.1, 0.9, 1e-4, P, 1, so, pe)
+    b = O.sgd_fused_mix_f64(x, v, g, 0.1, 0.9, 1e-4, P, so, pe)
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all()
+
+
+def test_hier_sgd_one_group_is_allreduce_sgd():
+    # One group: the leader steps on the gradient averaged over all workers and everybody
+    # copies the result -- the AllReduce-SGD baseline; check against the library optimizer.
+    import torch
+    W, P = 8, 30
+    lr, mu, wd = 0.1, 0.9, 1e-4
+    x = WL.gen_matrix(W, P, 0.05, 21)
+    v = WL.gen_matrix(1, P, 0.01, 21, stream=1)
+    g = WL.gen_matrix(W, P, 0.01, 21, stream=2)
+    xo, vo = O.hier_sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, W, [0, P], None)
+    q = torch.nn.Parameter(torch.from_numpy(x[0].copy()).double())
+    opt = torch.optim.SGD([q], lr=float(F(lr)), momentum=float(F(mu)), weight_decay=float(F(wd)))
+    opt.state[q]["momentum_buffer"] = torch.from_numpy(v[0].copy()).double()
+    q.grad = torch.from_numpy(g.astype(np.float64).mean(0))
+    opt.step()
+    assert np.abs(xo - q.detach().numpy()[None, :]).max() < 1e-15
+    assert np.abs(vo[0] - opt.state[q]["momentum_buffer"].numpy()).max() < 1e-15
+    x32, v32 = O.hier_sgd_fused_mix_f32(x, v, g, lr, mu, wd, P, W, [0, P], None)
+    assert np.abs(x32 - xo).max() < 1e-6 * np.abs(x).max()
+
+
+def test_hier_sgd_equal_gradients_and_lr0_reduce_to_known_cases():
+    W, G, P, S = 12, 4, 40, 2
+    L = W // G
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(22, L, S, 0, 1)[0]
+    xl = WL.gen_matrix(L, P, 0.05, 22)
+    x = np.repeat(xl, G, axis=0)
+    v = WL.gen_matrix(L, P, 0.01, 22, stream=1)
+    gl = WL.gen_matrix(L, P, 0.01, 22, stream=2)
+    g = np.repeat(gl, G, axis=0)                    # identical gradients inside a group
+    xo, vo = O.hier_sgd_fused_mix_f32(x, v, g, 0.1, 0.9, 1e-4, P, G, so, pe)
+    fx, fv = O.sgd_fused_mix_f32(xl, v, gl, 0.1, 0.9, 1e-4, P, so, pe)   # the leaders alone
+    assert (xo == np.repeat(fx, G, axis=0)).all() and (vo == fv).all()
+    # lr = 0: parameters only gossip between leaders and are broadcast
+    x0, _ = O.hier_sgd_fused_mix_f32(x, v, g, 0.0, 0.9, 1e-4, P, G, so, pe)
+    assert (x0 == O.hier_mix_f32(x, P, G, so, pe)).all()
+    # member rows of x are never read
+    junk = x.copy()
+    junk[1::G] = 1e9
+    xj, vj = O.hier_sgd_fused_mix_f32(junk, v, g, 0.1, 0.9, 1e-4, P, G, so, pe)
+    assert (xj == xo).all() and (vj == vo).all()
