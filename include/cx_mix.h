@@ -164,6 +164,28 @@ int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *
                      const int32_t *peers_dev, uint32_t flags, void *stream);
 
 /* ------------------------------------------------------------------------------------
+ * cx_hier_sgd_fused_mix -- hierarchical Crossover-SGD exactly as Section 3.3 states it:
+ * (1) the gradients of the G workers of a group are reduced at the group's leader, which
+ * applies them to its model; (2) the L = W / G leaders gossip segment-wise (Algorithm 1);
+ * (3) each leader's result is broadcast to its group.
+ *     gbar_q = (pairwise-tree fp32 sum of the group's G gradient rows) * (1.0f / G)
+ *     t = gbar_q + wd * x_q ;  v'_q = mu * v_q + t ;  h_q = x_q - lr * v'_q     (x_q = leader row)
+ *     y_q = (h_q + h_{leader_peers[s][q]}) * 0.5f                        (skipped when L == 1)
+ *     every row of group q  <-  y_q ;  v_out[q] = v'_q
+ *   x_in, x_out, g   float32 [W][ld]; of x_in only the leader rows (q * G) are read
+ *   v_in, v_out      float32 [L][ld]: the leaders' momentum
+ * x_out may equal x_in and v_out may equal v_in (then both must); with L == 1 this is
+ * AllReduce-SGD.  Per worker-parameter it moves 8 + 12/G bytes (read g, write x; the leader
+ * also reads x, v and writes v).
+ * Errors: as cx_hier_mix (group sizes 1, 2, 4, 8); CX_ERR_ALIAS also if exactly one of x, v is
+ * updated in place, or v overlaps x or g.
+ */
+int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *v_out,
+                          const float *g, float lr, float mu, float wd, int64_t ld, int32_t W,
+                          int64_t P, int32_t G, int32_t S, const int64_t *seg_off_dev,
+                          const int32_t *leader_peers_dev, uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method).
  * cx_copy_baseline: dst[i] = src[i] for n floats (n % 4 == 0, 16-byte aligned) with the
  * same load/store instructions as the mixing kernels; the practical HBM ceiling and the

@@ -217,6 +217,53 @@ struct FusedOp {
     }
 };
 
+// Hierarchical step with gradients: a gossiping row is a group; loading it reduces the G
+// gradient rows (pairwise tree), applies the momentum-SGD step to the LEADER's parameters
+// and momentum, and hands the updated leader parameters to the walk; storing broadcasts.
+template <int G>
+struct HierFusedOp {
+    static constexpr int kRawPerSlice = G + 2;
+    template <int U> struct Raw { Tile<U> g[G], x, v; };
+    const float *xin;
+    float *xout;
+    const float *vin;     // [L][ld]
+    float *vout;          // [L][ld]
+    const float *g;       // [W][ld]
+    int64_t ld;
+    float lr, mu, wd, inv_g;
+
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
+    {
+        const int64_t lead = static_cast<int64_t>(row) * G * ld + off;
+#pragma unroll
+        for (int j = 0; j < G; ++j) tile_load<U, FULL, NT>(g + lead + j * ld, mask, raw.g[j]);
+        tile_load<U, FULL, NT>(xin + lead, mask, raw.x);
+        tile_load<U, FULL, NT>(vin + static_cast<int64_t>(row) * ld + off, mask, raw.v);
+    }
+    template <int U, bool FULL, bool NT, bool COMMIT = true>
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Tile<U> &t) const
+    {
+        const Tile<U> gsum = tree_sum<G, U>(raw.g);
+        Tile<U> v;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const f4 gbar = gsum.v[u] * inv_g;
+            const f4 decayed = gbar + raw.x.v[u] * wd;
+            v.v[u] = raw.v.v[u] * mu + decayed;
+            t.v[u] = raw.x.v[u] - v.v[u] * lr;
+        }
+        if constexpr (COMMIT) tile_store<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v);
+    }
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Tile<U> &t) const
+    {
+        float *p = xout + static_cast<int64_t>(row) * G * ld + off;
+#pragma unroll
+        for (int j = 0; j < G; ++j) tile_store<U, FULL, NT>(p + j * ld, mask, t);
+    }
+};
+
 // Push-sum: plain rows, optional de-biased copy z = x' / w'.
 struct PushOp {
     static constexpr int kRawPerSlice = 1;
@@ -930,6 +977,46 @@ int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *
     const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream),
                     x_in != x_out && v_in != v_out, 1};
     return launch_mix<FusedOp, 1, 4>(op, a);
+}
+
+int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *v_out,
+                          const float *g, float lr, float mu, float wd, int64_t ld, int32_t W,
+                          int64_t P, int32_t G, int32_t S, const int64_t *seg_off_dev,
+                          const int32_t *leader_peers_dev, uint32_t flags, void *stream)
+{
+    if (!seg_off_dev || !x_in || !x_out || !v_in || !v_out || !g) return CX_ERR_NULL;
+    if (W < 1 || G < 1 || W % G != 0) return CX_ERR_SHAPE;
+    const int32_t L = W / G;
+    if (L > CX_MAX_ROWS) return CX_ERR_SHAPE;
+    if (L > 1 && !leader_peers_dev) return CX_ERR_NULL;
+    int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
+    if (rc != CX_OK) return rc;
+    rc = check_matrix_args(v_in, v_out, ld, L, P, S, flags);
+    if (rc != CX_OK) return rc;
+    if (misaligned(g)) return CX_ERR_ALIGN;
+    if ((x_in == x_out) != (v_in == v_out)) return CX_ERR_ALIAS;
+    const uint64_t xbytes = static_cast<uint64_t>(W) * ld * 4u, vbytes = static_cast<uint64_t>(L) * ld * 4u;
+    // v against x and g (ranges of different length: test with the longer one from the x/g side)
+    const auto overlap2 = [](const void *a, uint64_t na, const void *b, uint64_t nb) {
+        const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+        return x < y ? (y - x) < na : (x - y) < nb;
+    };
+    if (overlap2(x_in, xbytes, v_in, vbytes) || overlap2(x_in, xbytes, v_out, vbytes) ||
+        overlap2(x_out, xbytes, v_in, vbytes) || overlap2(x_out, xbytes, v_out, vbytes) ||
+        overlap2(g, xbytes, v_out, vbytes) || any_overlap(g, x_out, xbytes))
+        return CX_ERR_ALIAS;
+    const hipStream_t st = static_cast<hipStream_t>(stream);
+    const float inv_g = 1.0f / static_cast<float>(G);
+    const int skip = (L == 1) ? 1 : 0;
+    const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
+    const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
+    switch (G) {
+    case 1: return launch_mix<HierFusedOp<1>, 1, 4>(HierFusedOp<1>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    case 2: return launch_mix<HierFusedOp<2>, 1, 4>(HierFusedOp<2>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    case 4: return launch_mix<HierFusedOp<4>, 1, 4>(HierFusedOp<4>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    case 8: return launch_mix<HierFusedOp<8>, 1, 2>(HierFusedOp<8>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    default: return CX_ERR_UNSUPPORTED;
+    }
 }
 
 int cx_copy_baseline(const float *src, float *dst, int64_t n, void *stream)

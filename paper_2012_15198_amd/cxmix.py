@@ -27,7 +27,8 @@ TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE, TUNE_ORDERED = 4, 
 
 EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_segments",
            "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",
-           "cx_sgd_fused_mix", "cx_copy_baseline", "cx_set_tuning", "cx_get_tuning"]
+           "cx_sgd_fused_mix", "cx_hier_sgd_fused_mix", "cx_copy_baseline", "cx_set_tuning",
+           "cx_get_tuning"]
 
 
 class CxError(RuntimeError):
@@ -62,6 +63,8 @@ def lib() -> ctypes.CDLL:
     L.cx_pushsum_mix.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, u32, vp]
     L.cx_sgd_fused_mix.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32,
                                    vp, vp, u32, vp]
+    L.cx_hier_sgd_fused_mix.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32,
+                                        vp, vp, u32, vp]
     L.cx_copy_baseline.argtypes = [vp, vp, i64, vp]
     L.cx_set_tuning.argtypes = [i32, i32]
     L.cx_get_tuning.argtypes = [i32]
@@ -168,6 +171,18 @@ def cx_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: floa
                                                    _dptr(v_out), _dptr(g), lr, mu, wd, ld, W, P,
                                                    S, _dptr(seg_off_dev), _dptr(peers_dev), flags,
                                                    _stream(stream)))
+
+
+def cx_hier_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: float, P: int,
+                          G: int, seg_off_dev, leader_peers_dev, flags: int = 0, stream=None):
+    """x, g: [W][ld]; v: [W/G][ld] with the same ld (see include/cx_mix.h)."""
+    W, ld = _shape(x_in)
+    if v_in.dim() != 2 or v_in.stride(0) != ld or g.stride(0) != ld:
+        raise ValueError("x, v and g must share one leading dimension")
+    S = seg_off_dev.numel() - 1
+    _ok("cx_hier_sgd_fused_mix", lib().cx_hier_sgd_fused_mix(
+        _dptr(x_in), _dptr(x_out), _dptr(v_in), _dptr(v_out), _dptr(g), lr, mu, wd, ld, W, P, G, S,
+        _dptr(seg_off_dev), _dptr(leader_peers_dev), flags, _stream(stream)))
 
 
 def cx_copy_baseline(src, dst, stream=None):

@@ -169,6 +169,43 @@ def test_c4_fused_sgd_sampled_all_rounds():
     free(x, x2, v, v2, g)
 
 
+def test_c3_shape_hierarchical_gradient_step_sampled_all_rounds():
+    """Section 3.3 as printed (gradients reduced at the leader) on the C3 shape, optimizer
+    constants and gradient scale of C4."""
+    wl, c4 = WL.WORKLOADS["C3"], WL.WORKLOADS["C4"]
+    lr, mu, wd = c4.lr, c4.mu, c4.wd
+    so = WL.seg_off_for(wl)
+    ld = padded(wl.P)
+    tabs = cx.cx_topology_gen(wl.seed, wl.L, wl.S, 0, wl.rounds)
+    x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld)
+    g = WL.gen_matrix_device(wl.W, wl.P, c4.grad_sigma, wl.seed, ld=ld, stream=2)
+    v = torch.zeros((wl.L, ld), device=x.device)
+    x2, v2 = torch.empty_like(x), torch.empty_like(v)
+    cols, sso, cold = sample(wl, so)
+    sx, sv, sg = take(x, cold), take(v, cold), take(g, cold)
+    sod = dev(so)
+    n = len(cols)
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        if r % 2 == 0:
+            cx.cx_hier_sgd_fused_mix(x, x2, v, v2, g, lr, mu, wd, wl.P, wl.G, sod, t)
+            x, x2, v, v2 = x2, x, v2, v
+        else:
+            cx.cx_hier_sgd_fused_mix(x, x, v, v, g, lr, mu, wd, wl.P, wl.G, sod, t)
+        bx, bv = sx, sv
+        sx, sv = O.hier_sgd_fused_mix_f32(sx, sv, sg, lr, mu, wd, n, wl.G, sso, tabs[r])
+        ax, av = take(x, cold), take(v, cold)
+        assert same_bits(ax, sx) and same_bits(av, sv), r
+        x64, v64 = O.hier_sgd_fused_mix_f64(bx, bv, sg, lr, mu, wd, n, wl.G, sso, tabs[r])
+        m = np.abs(bx[::wl.G].astype(np.float64)) + lr * (mu * np.abs(bv) + np.abs(sg).reshape(wl.L, wl.G, n).mean(1)
+                                                        + wd * np.abs(bx[::wl.G]))
+        scale = m.copy()
+        for s in range(wl.S):
+            scale[:, sso[s]:sso[s + 1]] = np.maximum(m[:, sso[s]:sso[s + 1]], m[tabs[r][s], sso[s]:sso[s + 1]])
+        assert (np.abs(ax - x64) <= REL * np.maximum(np.abs(x64), np.repeat(scale, wl.G, axis=0))).all(), r
+    free(x, x2, v, v2, g)
+
+
 def test_c4_pushsum_sampled_all_rounds():
     wl = WL.WORKLOADS["C4"]
     ld = padded(wl.P)

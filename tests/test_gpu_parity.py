@@ -266,6 +266,75 @@ def test_fused_lr0_is_gossip_and_rounds_track_oracle():
     assert same_bits(host(x0), O.gossip_mix(x, P, so, tabs[0]))
 
 
+# ------------------------------------------------ hierarchical step with gradients (Section 3.3)
+def hier_fused_scales(x, v, g, lr, mu, wd, G, seg_off, peers):
+    """As fused_scales, with the group-mean gradient magnitude and leader rows."""
+    W = x.shape[0]
+    L = W // G
+    xl = np.abs(x[::G].astype(np.float64))
+    gm = np.abs(g.astype(np.float64)).reshape(L, G, -1).mean(1)
+    n = mu * np.abs(v.astype(np.float64)) + gm + wd * xl
+    m = xl + lr * n
+    mp = m.copy()
+    if L > 1:
+        for s in range(len(seg_off) - 1):
+            c0, c1 = seg_off[s], seg_off[s + 1]
+            mp[:, c0:c1] = np.maximum(m[:, c0:c1], m[peers[s], c0:c1])
+    return np.repeat(mp, G, axis=0), n
+
+
+@pytest.mark.parametrize("W,G,P,ld,S", [(4, 1, 2100, 2100, 2), (8, 2, 3001, 3004, 3), (16, 4, 5003, 5004, 4),
+                                        (64, 8, 4099, 4100, 16), (8, 8, 2100, 2100, 3), (2, 2, 5, 8, 1)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_hier_sgd_fused_matches_fp64_reference_and_fixed_order_fp32(W, G, P, ld, S, inplace):
+    lr, mu, wd = 0.1, 0.9, 1e-4
+    L = W // G
+    x = WL.gen_matrix(W, P, 0.05, seed=61, ld=ld)
+    v = WL.gen_matrix(L, P, 0.01, seed=61, ld=ld, stream=1)
+    g = WL.gen_matrix(W, P, 0.01, seed=61, ld=ld, stream=2)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(61, L, S, 0, 1)[0] if L > 1 else None
+    xd, vd, gd = dev(x), dev(v), dev(g)
+    xo = xd if inplace else xd.clone()
+    vo = vd if inplace else vd.clone()
+    cx.cx_hier_sgd_fused_mix(xd, xo, vd, vo, gd, lr, mu, wd, P, G, dev(so), dev(pe) if L > 1 else None)
+    torch.cuda.synchronize()
+    gx, gv = host(xo), host(vo)
+    x64, v64 = O.hier_sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, G, so, pe)
+    xs, vs = hier_fused_scales(x[:, :P], v[:, :P], g[:, :P], lr, mu, wd, G, so, pe)
+    assert (np.abs(gx[:, :P] - x64[:, :P]) <= REL * np.maximum(np.abs(x64[:, :P]), xs)).all()
+    assert (np.abs(gv[:, :P] - v64[:, :P]) <= REL * np.maximum(np.abs(v64[:, :P]), vs)).all()
+    x32, v32 = O.hier_sgd_fused_mix_f32(x, v, g, lr, mu, wd, P, G, so, pe)
+    assert same_bits(gx, x32) and same_bits(gv, v32)
+    assert same_bits(host(gd), g)
+
+
+@pytest.mark.parametrize("tuning", ALL_TUNINGS)
+def test_hier_sgd_fused_rounds_under_every_launch_shape(tuning):
+    W, G, P, S, R = 32, 8, 6007, 5, 3
+    lr, mu, wd = 0.1, 0.9, 1e-4
+    L = W // G
+    x = WL.gen_matrix(W, P, 0.05, seed=62, ld=6008)
+    v = np.zeros((L, 6008), dtype=np.float32)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(62, L, S, 0, R)
+    gs = [WL.gen_matrix(W, P, 0.01, seed=62, ld=6008, stream=10 + r) for r in range(R)]
+    wx, wv = x, v
+    for r in range(R):
+        wx, wv = O.hier_sgd_fused_mix_f32(wx, wv, gs[r], lr, mu, wd, P, G, so, tabs[r])
+    with Tuning(*tuning):
+        xd, vd = dev(x), dev(v)
+        y0, y1, u0, u1 = dev(x), dev(x), dev(v), dev(v)
+        for r in range(R):
+            gd = dev(gs[r])
+            cx.cx_hier_sgd_fused_mix(xd, xd, vd, vd, gd, lr, mu, wd, P, G, dev(so), dev(tabs[r]))
+            cx.cx_hier_sgd_fused_mix(y0, y1, u0, u1, gd, lr, mu, wd, P, G, dev(so), dev(tabs[r]))
+            y0, y1, u0, u1 = y1, y0, u1, u0
+        torch.cuda.synchronize()
+    assert same_bits(host(xd), wx) and same_bits(host(vd), wv)
+    assert same_bits(host(y0), wx) and same_bits(host(u0), wv)
+
+
 # ---------------------------------------------------------------------------- push-sum
 @pytest.mark.parametrize("W,P,ld,hop", [(2, 5, 8, 1), (8, 5003, 5004, 1), (8, 5003, 5004, 4),
                                         (6, 3000, 3000, 4), (128, 1100, 1100, 64), (13, 2049, 2052, 8)])

@@ -119,6 +119,18 @@ def test_mix_calls_reject_bad_arguments_on_the_host():
     assert fused(v_in=A) == -6 and fused(v_out=B) == -6 and fused(g=B) == -6
     assert fused(v_out=C + 32) == -6 and fused(g=D + 4) == -5 and fused(W=1) == -2
 
+    def hfused(G=2, v_in=C, v_out=C, x_out=A, g=D, pe=T2, **kw):
+        a = {**ok, **kw}
+        return L.cx_hier_sgd_fused_mix(a["x_in"], x_out, v_in, v_out, g, 0.1, 0.9, 1e-4, a["ld"], a["W"],
+                                       a["P"], G, a["S"], a["so"], pe, a["flags"], a["st"])
+
+    assert hfused(g=None) == -1 and hfused(v_in=None) == -1 and hfused(pe=None) == -1
+    assert hfused(G=3) == -2 and hfused(G=0) == -2
+    assert hfused(x_out=B) == -6                       # x out of place but v in place
+    assert hfused(v_out=E) == -6                       # v out of place but x in place
+    assert hfused(v_in=A, v_out=A) == -6 and hfused(g=A) == -6 and hfused(g=C) == -6
+    assert hfused(G=16, W=32) == -8 and hfused(g=D + 4) == -5
+
     assert L.cx_copy_baseline(None, B, 64, None) == -1
     assert L.cx_copy_baseline(A, B, 6, None) == -2
     assert L.cx_copy_baseline(A, A + 64, 64, None) == -6
