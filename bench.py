@@ -54,7 +54,7 @@ class Runner:
         self.ld = (wl.P + 1023) // 1024 * 1024
         self.x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=self.ld, device=dev)
         self.y = self.x if in_place else torch.empty_like(self.x)
-        self.n = wl.L if kind == "hier" else wl.W
+        self.n = wl.L if kind in ("hier", "hiersgd") else wl.W
         self.S = 1 if kind == "pushsum" else wl.S
         self.mode = 1 if kind == "pushsum" else 0
         # one pinned + one device slot per round, so the host can run ahead of the GPU
@@ -67,6 +67,13 @@ class Runner:
             self.v2 = self.v if in_place else torch.empty_like(self.v)
             self.g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
             self.bytes_per_elem = 20
+        if kind == "hiersgd":
+            c4 = WL.WORKLOADS["C4"]            # optimizer constants and gradient scale of C4
+            self.lr, self.mu, self.wd = c4.lr, c4.mu, c4.wd
+            self.bytes_per_elem = 8 + 12.0 / wl.G
+            self.v = torch.zeros((wl.L, self.ld), device=dev)
+            self.v2 = self.v if in_place else torch.empty_like(self.v)
+            self.g = WL.gen_matrix_device(wl.W, wl.P, c4.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
         if kind == "pushsum":
             self.w = [torch.ones(wl.W, device=dev), torch.zeros(wl.W, device=dev)]
         self.round = 0
@@ -88,6 +95,10 @@ class Runner:
         elif self.kind == "fused":
             cx.cx_sgd_fused_mix(self.x, self.y, self.v, self.v2, self.g, wl.lr, wl.mu, wl.wd, wl.P,
                                 self.so, tab)
+            self.v, self.v2 = self.v2, self.v
+        elif self.kind == "hiersgd":
+            cx.cx_hier_sgd_fused_mix(self.x, self.y, self.v, self.v2, self.g, self.lr, self.mu, self.wd,
+                                     wl.P, wl.G, self.so, tab)
             self.v, self.v2 = self.v2, self.v
         elif self.kind == "pushsum":
             hop = int((0 - int(self.tab_np[r, 0, 0])) % wl.W)
@@ -111,7 +122,7 @@ class Runner:
         kernel_ms = [a.elapsed_time(b) for a, b in self.ev]
         wl = self.wl
         elems = wl.W * wl.P
-        alg_bytes = elems * self.bytes_per_elem
+        alg_bytes = int(elems * self.bytes_per_elem)
         ms_step = wall * 1e3 / steps
         k_avg = float(np.mean(kernel_ms))
         return {
@@ -187,7 +198,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C2")
-    ap.add_argument("--kind", default=None, choices=[None, "gossip", "hier", "fused", "pushsum"],
+    ap.add_argument("--kind", default=None, choices=[None, "gossip", "hier", "fused", "pushsum", "hiersgd"],
                     help="entry point to time (default: the workload's own; C4 has fused and pushsum)")
     ap.add_argument("--all", action="store_true", help="also time the other workloads' entry points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -215,7 +226,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": describe(wl) if kind != "gossip" or wl.G == 1 else describe(wl) + " (flat gossip over all rows)",
-                   "entry_point": f"cx_{kind}_mix" if kind != "fused" else "cx_sgd_fused_mix",
+                   "entry_point": {"fused": "cx_sgd_fused_mix", "hiersgd": "cx_hier_sgd_fused_mix"}.get(kind, f"cx_{kind}_mix"),
                    "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
                    "buffers": "in place" if args.in_place else "ping-pong (x_in -> x_out, swapped every round)",
                    "step": "cx_topology_gen(1 round) + table upload + one mixing launch"},
@@ -240,8 +251,8 @@ def main():
 
     if args.all:
         others = {}
-        plan = [("C1", "gossip", 50), ("C3", "hier", 20), ("C4", "fused", 10), ("C4", "pushsum", 20),
-                ("C5", "hier", 10)]
+        plan = [("C1", "gossip", 50), ("C3", "hier", 20), ("C3", "hiersgd", 20), ("C4", "fused", 10),
+                ("C4", "pushsum", 20), ("C5", "hier", 10)]
         for name, k, steps in plan:
             if name == args.workload and k == kind:
                 continue

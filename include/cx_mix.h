@@ -45,10 +45,11 @@
  *              Device tables are NOT read by the host: check their host mirrors with
  *              cx_check_segments / cx_check_peers before uploading.
  *   scratch    the out-of-place kernels keep a row-order table in library-owned device
- *              memory (static, 8 slots of 1 MiB per GPU), so no call allocates.  A slot is
- *              bound to the stream that first uses it; calls on one stream run in order, so
- *              a table is never rewritten while it is read.  Calls on a ninth and later
- *              stream run without the table: same results, lower speed.
+ *              memory (static, per entry point 4 slots of 1 MiB per GPU), so no call
+ *              allocates.  A slot is bound to the stream that first uses it; calls on one
+ *              stream run in order, so a table is never rewritten while it is read.  Calls
+ *              of one entry point on a fifth and later stream run without the table: same
+ *              results, lower speed.
  *   limits     at most CX_MAX_ROWS gossiping rows (W, or W/G in hierarchical mode).
  *   return     CX_OK (0) or a negative cx_status.  Argument errors are detected on the host
  *              before anything is enqueued.

@@ -1,0 +1,32 @@
+// C-ABI entry point(s) cx_hier_mix: argument checks and launch (see include/cx_mix.h).
+#include "cx_kernels.hpp"
+
+extern "C" {
+
+int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P, int32_t G,
+                int32_t S, const int64_t *seg_off_dev, const int32_t *leader_peers_dev,
+                uint32_t flags, void *stream)
+{
+    if (!seg_off_dev || !x_in || !x_out) return CX_ERR_NULL;
+    if (W < 1 || G < 1 || W % G != 0) return CX_ERR_SHAPE;
+    const int32_t L = W / G;
+    if (L > CX_MAX_ROWS) return CX_ERR_SHAPE;
+    if (L > 1 && !leader_peers_dev) return CX_ERR_NULL;
+    const int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
+    if (rc != CX_OK) return rc;
+    const hipStream_t st = static_cast<hipStream_t>(stream);
+    const float inv_g = 1.0f / static_cast<float>(G);
+    const int skip = (L == 1) ? 1 : 0;
+    const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
+    const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
+    switch (G) {
+    case 1: return launch_mix<MeanOp<1>, 2, 4>(MeanOp<1>{x_in, x_out, ld, inv_g}, a);
+    case 2: return launch_mix<MeanOp<2>, 2, 4>(MeanOp<2>{x_in, x_out, ld, inv_g}, a);
+    case 4: return launch_mix<MeanOp<4>, 1, 4>(MeanOp<4>{x_in, x_out, ld, inv_g}, a);
+    case 8: return launch_mix<MeanOp<8>, 1, 4>(MeanOp<8>{x_in, x_out, ld, inv_g}, a);
+    case 16: return launch_mix<MeanOp<16>, 1, 2>(MeanOp<16>{x_in, x_out, ld, inv_g}, a);
+    default: return CX_ERR_UNSUPPORTED;
+    }
+}
+
+}  // extern "C"

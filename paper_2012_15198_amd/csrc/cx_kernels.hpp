@@ -1,5 +1,8 @@
 // Device half of the gossip-mixing library for gfx950 (MI355X): the mixing kernels behind
-// cx_gossip_mix / cx_hier_mix / cx_pushsum_mix / cx_sgd_fused_mix and their C-ABI launchers.
+// cx_gossip_mix / cx_hier_mix / cx_pushsum_mix / cx_sgd_fused_mix / cx_hier_sgd_fused_mix and
+// their launch logic.  Internal header: each cx_api_*.hip includes it and defines one entry
+// point, so the operators compile in parallel; everything here has internal linkage (each
+// translation unit carries its own row-order table).
 //
 // Mixing is independent per column and every element has to be read once and written once
 // (8 B per worker-parameter; 20 B with the fused optimizer), so the whole path is bound by
@@ -34,6 +37,8 @@
 //  segment with per-element predication.  Row operators (MeanOp / FusedOp / PushOp) say
 //  what loading and storing a "gossiping row" means: the pairwise-tree mean of a group of
 //  G rows, the momentum-SGD update applied on the way in, or the push-sum de-biasing.
+#ifndef CX_KERNELS_HPP
+#define CX_KERNELS_HPP
 #include "cx_mix.h"
 
 #include <hip/hip_runtime.h>
@@ -485,11 +490,11 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
 // ---------------------------------------------------------------------------------
 // Row order of the out-of-place path.  Library-owned device memory (no allocation at run
 // time): kOrderSlots tables of kOrderEntries ints per GPU.  A slot belongs to ONE stream
-// (first come, first served, for the life of the process): calls on a stream run in stream
+// and one entry point (first come, first served, for the life of the process): calls on a stream run in stream
 // order, so a slot is never rewritten while an earlier call still reads it.  Streams beyond
 // the first kOrderSlots run without a table (natural row order: same results, slower).
 // ---------------------------------------------------------------------------------
-constexpr int kOrderSlots = 8;
+constexpr int kOrderSlots = 4;
 constexpr int kOrderEntries = 1 << 18;
 __device__ int g_order[kOrderSlots][kOrderEntries];
 
@@ -666,36 +671,6 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     }
 }
 
-// w_out[i] = (w_in[i] + w_in[(i - hop) mod n]) * 0.5f  (push-sum weights, n <= CX_MAX_ROWS)
-__global__ void pushsum_weight_kernel(const float *__restrict__ w_in, float *__restrict__ w_out,
-                                      int n, int hop)
-{
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-        const int from = i >= hop ? i - hop : i - hop + n;
-        w_out[i] = (w_in[i] + w_in[from]) * 0.5f;
-    }
-}
-
-template <int U, bool NT>
-__global__ __launch_bounds__(256) void copy_kernel(const float *src, float *dst, int64_t ntiles,
-                                                   int64_t nslices)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = uniform(threadIdx.x >> 6);
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;
-    if (tile >= ntiles) return;
-    const int64_t first = tile * (64 * U) + lane;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t q = first + u * 64;
-        if (q < nslices) {
-            const f4 *s = reinterpret_cast<const f4 *>(src) + q;
-            f4 *d = reinterpret_cast<f4 *>(dst) + q;
-            if (NT) __builtin_nontemporal_store(__builtin_nontemporal_load(s), d); else *d = *s;
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------
@@ -718,16 +693,16 @@ Launch pick_launch(int default_u, int default_d)
     return l;
 }
 
-bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+[[maybe_unused]] bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // true if the byte ranges [a, a+bytes) and [b, b+bytes) overlap without being identical
-bool partial_overlap(const void *a, const void *b, uint64_t bytes)
+[[maybe_unused]] bool partial_overlap(const void *a, const void *b, uint64_t bytes)
 {
     const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
     if (x == y) return false;
     return x < y ? (y - x) < bytes : (x - y) < bytes;
 }
-bool any_overlap(const void *a, const void *b, uint64_t bytes)
+[[maybe_unused]] bool any_overlap(const void *a, const void *b, uint64_t bytes)
 {
     return a == b || partial_overlap(a, b, bytes);
 }
@@ -893,153 +868,4 @@ int check_matrix_args(const void *x_in, const void *x_out, int64_t ld, int64_t r
 
 }  // namespace
 
-extern "C" {
-
-int cx_gossip_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P, int32_t S,
-                  const int64_t *seg_off_dev, const int32_t *peers_dev, uint32_t flags,
-                  void *stream)
-{
-    if (!seg_off_dev || !peers_dev) return CX_ERR_NULL;
-    if (W < 2 || W > CX_MAX_ROWS) return (!x_in || !x_out) ? CX_ERR_NULL : CX_ERR_SHAPE;
-    const int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
-    if (rc != CX_OK) return rc;
-    const MeanOp<1> op{x_in, x_out, ld, 1.0f};
-    const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream), x_in != x_out, 1};
-    return launch_mix<MeanOp<1>, 4, 2>(op, a);
-}
-
-int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P, int32_t G,
-                int32_t S, const int64_t *seg_off_dev, const int32_t *leader_peers_dev,
-                uint32_t flags, void *stream)
-{
-    if (!seg_off_dev || !x_in || !x_out) return CX_ERR_NULL;
-    if (W < 1 || G < 1 || W % G != 0) return CX_ERR_SHAPE;
-    const int32_t L = W / G;
-    if (L > CX_MAX_ROWS) return CX_ERR_SHAPE;
-    if (L > 1 && !leader_peers_dev) return CX_ERR_NULL;
-    const int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
-    if (rc != CX_OK) return rc;
-    const hipStream_t st = static_cast<hipStream_t>(stream);
-    const float inv_g = 1.0f / static_cast<float>(G);
-    const int skip = (L == 1) ? 1 : 0;
-    const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
-    const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
-    switch (G) {
-    case 1: return launch_mix<MeanOp<1>, 2, 4>(MeanOp<1>{x_in, x_out, ld, inv_g}, a);
-    case 2: return launch_mix<MeanOp<2>, 2, 4>(MeanOp<2>{x_in, x_out, ld, inv_g}, a);
-    case 4: return launch_mix<MeanOp<4>, 1, 4>(MeanOp<4>{x_in, x_out, ld, inv_g}, a);
-    case 8: return launch_mix<MeanOp<8>, 1, 4>(MeanOp<8>{x_in, x_out, ld, inv_g}, a);
-    case 16: return launch_mix<MeanOp<16>, 1, 2>(MeanOp<16>{x_in, x_out, ld, inv_g}, a);
-    default: return CX_ERR_UNSUPPORTED;
-    }
-}
-
-int cx_pushsum_mix(const float *x_in, float *x_out, const float *w_in, float *w_out, float *z_out,
-                   int64_t ld, int32_t W, int64_t P, int32_t hop, uint32_t flags, void *stream)
-{
-    if (!w_in || !w_out || !x_in || !x_out) return CX_ERR_NULL;
-    if (W < 2 || W > CX_MAX_ROWS || hop < 1 || hop >= W) return CX_ERR_SHAPE;
-    const int rc = check_matrix_args(x_in, x_out, ld, W, P, 1, flags);
-    if (rc != CX_OK) return rc;
-    const uint64_t bytes = static_cast<uint64_t>(W) * ld * 4u;
-    if (any_overlap(w_in, w_out, static_cast<uint64_t>(W) * 4u)) return CX_ERR_ALIAS;
-    if (z_out) {
-        if (misaligned(z_out)) return CX_ERR_ALIGN;
-        if (any_overlap(z_out, x_in, bytes) || any_overlap(z_out, x_out, bytes)) return CX_ERR_ALIAS;
-    }
-    const hipStream_t st = static_cast<hipStream_t>(stream);
-    // the de-biasing reads w_in, so the weights are written by their own tiny launch
-    hipLaunchKernelGGL(pushsum_weight_kernel, dim3(1), dim3(256), 0, st, w_in, w_out, W, hop);
-    if (hipGetLastError() != hipSuccess) return CX_ERR_HIP;
-    const PushOp op{x_in, x_out, z_out, w_in, ld, W, hop};
-    const MixArgs a{W, P, 1, /*seg_off: unused for S == 1*/ nullptr, nullptr, hop, 0, st, x_in != x_out, 1};
-    return launch_mix<PushOp, 2, 4>(op, a);
-}
-
-int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *v_out,
-                     const float *g, float lr, float mu, float wd, int64_t ld, int32_t W,
-                     int64_t P, int32_t S, const int64_t *seg_off_dev, const int32_t *peers_dev,
-                     uint32_t flags, void *stream)
-{
-    if (!seg_off_dev || !peers_dev || !v_in || !v_out || !g) return CX_ERR_NULL;
-    if (W < 2 || W > CX_MAX_ROWS) return (!x_in || !x_out) ? CX_ERR_NULL : CX_ERR_SHAPE;
-    int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
-    if (rc != CX_OK) return rc;
-    rc = check_matrix_args(v_in, v_out, ld, W, P, S, flags);
-    if (rc != CX_OK) return rc;
-    if (misaligned(g)) return CX_ERR_ALIGN;
-    const uint64_t bytes = static_cast<uint64_t>(W) * ld * 4u;
-    if (any_overlap(x_in, v_in, bytes) || any_overlap(x_in, v_out, bytes) ||
-        any_overlap(x_out, v_in, bytes) || any_overlap(x_out, v_out, bytes) ||
-        any_overlap(g, x_out, bytes) || any_overlap(g, v_out, bytes))
-        return CX_ERR_ALIAS;
-    const FusedOp op{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd};
-    const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream),
-                    x_in != x_out && v_in != v_out, 1};
-    return launch_mix<FusedOp, 1, 4>(op, a);
-}
-
-int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *v_out,
-                          const float *g, float lr, float mu, float wd, int64_t ld, int32_t W,
-                          int64_t P, int32_t G, int32_t S, const int64_t *seg_off_dev,
-                          const int32_t *leader_peers_dev, uint32_t flags, void *stream)
-{
-    if (!seg_off_dev || !x_in || !x_out || !v_in || !v_out || !g) return CX_ERR_NULL;
-    if (W < 1 || G < 1 || W % G != 0) return CX_ERR_SHAPE;
-    const int32_t L = W / G;
-    if (L > CX_MAX_ROWS) return CX_ERR_SHAPE;
-    if (L > 1 && !leader_peers_dev) return CX_ERR_NULL;
-    int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
-    if (rc != CX_OK) return rc;
-    rc = check_matrix_args(v_in, v_out, ld, L, P, S, flags);
-    if (rc != CX_OK) return rc;
-    if (misaligned(g)) return CX_ERR_ALIGN;
-    if ((x_in == x_out) != (v_in == v_out)) return CX_ERR_ALIAS;
-    const uint64_t xbytes = static_cast<uint64_t>(W) * ld * 4u, vbytes = static_cast<uint64_t>(L) * ld * 4u;
-    // v against x and g (ranges of different length: test with the longer one from the x/g side)
-    const auto overlap2 = [](const void *a, uint64_t na, const void *b, uint64_t nb) {
-        const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-        return x < y ? (y - x) < na : (x - y) < nb;
-    };
-    if (overlap2(x_in, xbytes, v_in, vbytes) || overlap2(x_in, xbytes, v_out, vbytes) ||
-        overlap2(x_out, xbytes, v_in, vbytes) || overlap2(x_out, xbytes, v_out, vbytes) ||
-        overlap2(g, xbytes, v_out, vbytes) || any_overlap(g, x_out, xbytes))
-        return CX_ERR_ALIAS;
-    const hipStream_t st = static_cast<hipStream_t>(stream);
-    const float inv_g = 1.0f / static_cast<float>(G);
-    const int skip = (L == 1) ? 1 : 0;
-    const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
-    const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
-    switch (G) {
-    case 1: return launch_mix<HierFusedOp<1>, 1, 4>(HierFusedOp<1>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 2: return launch_mix<HierFusedOp<2>, 1, 4>(HierFusedOp<2>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 4: return launch_mix<HierFusedOp<4>, 1, 4>(HierFusedOp<4>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 8: return launch_mix<HierFusedOp<8>, 1, 2>(HierFusedOp<8>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    default: return CX_ERR_UNSUPPORTED;
-    }
-}
-
-int cx_copy_baseline(const float *src, float *dst, int64_t n, void *stream)
-{
-    if (!src || !dst) return CX_ERR_NULL;
-    if (n < 4 || (n & 3) != 0) return CX_ERR_SHAPE;
-    if (misaligned(src) || misaligned(dst)) return CX_ERR_ALIGN;
-    if (any_overlap(src, dst, static_cast<uint64_t>(n) * 4u)) return CX_ERR_ALIAS;
-    const Launch l = pick_launch(1, 2);
-    const int64_t nslices = n / 4;
-    const int64_t ntiles = (nslices + 64 * l.U - 1) / (64 * l.U);
-    const int64_t nblocks = (ntiles + 3) / 4;
-    if (nblocks > 0x7fffffffLL) return CX_ERR_SHAPE;
-    const dim3 grid(static_cast<unsigned>(nblocks)), block(256);
-    const hipStream_t st = static_cast<hipStream_t>(stream);
-#define CX_COPY(UU, NTT) hipLaunchKernelGGL((copy_kernel<UU, NTT>), grid, block, 0, st, src, dst, ntiles, nslices)
-    if (l.nt) {
-        if (l.U == 1) CX_COPY(1, true); else if (l.U == 2) CX_COPY(2, true); else CX_COPY(4, true);
-    } else {
-        if (l.U == 1) CX_COPY(1, false); else if (l.U == 2) CX_COPY(2, false); else CX_COPY(4, false);
-    }
-#undef CX_COPY
-    return hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
-}
-
-}  // extern "C"
+#endif  // CX_KERNELS_HPP
