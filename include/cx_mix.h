@@ -77,6 +77,14 @@ enum cx_status {
     CX_ERR_UNSUPPORTED = -8  /* valid request this build cannot serve (see each call) */
 };
 
+/* Topology modes of cx_topology_gen. */
+enum cx_topology_mode {
+    CX_TOPO_FAIR = 0,                /* Algorithm 2: random topology with fair peer selection */
+    CX_TOPO_DIRECTED_EXP = 1,        /* SGP's time-varying directed exponential graph */
+    CX_TOPO_UNFAIR = 2,              /* random topology without fair selection (duplicates) */
+    CX_TOPO_SAME_ALL_SEGMENTS = 16   /* OR-ed in: segment 0's table for every segment */
+};
+
 /* Human-readable name of a status code (static storage). */
 const char *cx_status_string(int status);
 
@@ -96,6 +104,12 @@ int cx_abi_version(void);
  *           and a run can be resumed at any round.
  *   mode 1  time-varying directed exponential graph of the SGP comparison: in round t
  *           row i receives from (i - 2^(t mod ceil(log2 n))) mod n, for every segment.
+ *   mode 2  the conventional random topology the paper compares with (Sections 3.2, 4.3):
+ *           row i draws uniformly among the other n-1 rows (draw index i), independently of
+ *           the other rows, so a row may be chosen several times or never.  Such a table is
+ *           not a permutation: mix with it out of place.
+ *   | 16    every segment of a round gets segment 0's table, which equals model-wise
+ *           communication (Section 3; the "without segment-wise" ablation of Section 4.3).
  *   peers_host  int32 [R][S][n], caller-allocated, written completely on success.
  * Errors: CX_ERR_NULL; CX_ERR_SHAPE if n < 2, n > CX_MAX_ROWS, S < 1, R < 0, round0 < 0
  * or round0 + R overflows; CX_ERR_UNSUPPORTED for an unknown mode.

@@ -103,24 +103,49 @@ int oracle_fair_draw(uint64_t key, int32_t n, int32_t *d)
 }
 
 /*
+ * The "conventional" random topology the paper compares with (Sections 3.2, 4.3):
+ * every rank draws its peer uniformly among the other n-1 ranks, independently, so
+ * a rank may be chosen several times or not at all (row-stochastic mixing matrix).
+ */
+int oracle_unfair_draw(uint64_t key, int32_t n, int32_t *d)
+{
+    if (n < 2) return -1;
+    for (int32_t i = 0; i < n; ++i) {
+        uint32_t t = oracle_uniform(oracle_draw(key, (uint32_t)i), (uint32_t)(n - 1));
+        d[i] = (int32_t)t < i ? (int32_t)t : (int32_t)t + 1;   /* t-th rank other than i */
+    }
+    return 0;
+}
+
+/*
  * Peer tables for rounds [round0, round0+R), S segments, n gossiping rows.
  * mode 0: fair random topology (Algorithm 2), a fresh one per (round, segment).
  * mode 1: time-varying directed exponential graph (the SGP comparison):
  *         in round t every row i receives from (i - 2^(t mod ceil(log2 n))) mod n,
  *         the same shift for every segment.
+ * mode 2: random topology without fair peer selection (duplicates allowed).
+ * mode + 16: the table of segment 0 is used for every segment of the round, which
+ *         Section 3 says equals model-wise communication.
  * out: int32 [R][S][n].
  */
 int oracle_topology(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t R,
                     int32_t mode, int32_t *out)
 {
     if (n < 2 || S < 1 || R < 0 || round0 < 0) return -1;
+    int same = (mode & 16) != 0;
+    mode &= ~16;
     int32_t nlog = 0;
     while (((int64_t)1 << nlog) < (int64_t)n) ++nlog;     /* ceil(log2 n) */
     for (int32_t r = 0; r < R; ++r) {
         for (int32_t s = 0; s < S; ++s) {
             int32_t *d = out + ((int64_t)r * S + s) * n;
-            if (mode == 0) {
+            if (same && s > 0) {
+                memcpy(d, out + (int64_t)r * S * n, sizeof(int32_t) * (size_t)n);
+            } else if (mode == 0) {
                 int rc = oracle_fair_draw(oracle_key(seed, round0 + r, s), n, d);
+                if (rc) return rc;
+            } else if (mode == 2) {
+                int rc = oracle_unfair_draw(oracle_key(seed, round0 + r, s), n, d);
                 if (rc) return rc;
             } else if (mode == 1) {
                 int64_t hop = (int64_t)1 << ((round0 + r) % nlog);

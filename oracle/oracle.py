@@ -119,7 +119,8 @@ def fair_draw(k: int, n: int) -> np.ndarray:
 
 
 def topology(seed: int, n: int, S: int, round0: int, R: int, mode: int = 0) -> np.ndarray:
-    """int32 [R][S][n] peer tables (mode 0: fair random, 1: directed exponential)."""
+    """int32 [R][S][n] peer tables (mode 0: fair random, 1: directed exponential, 2: random
+    without fair selection; +16: one table for all segments of a round)."""
     out = np.full((R, S, n), -1, dtype=np.int32)
     _check(_L().oracle_topology(seed & (2**64 - 1), n, S, round0, R, mode, _p(out)),
            "oracle_topology")

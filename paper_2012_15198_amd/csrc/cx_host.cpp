@@ -64,6 +64,16 @@ void fair_table(const DrawStream &rng, int32_t n, int32_t *recv_from, std::vecto
 }
 
 constexpr int kTuningKeys = 9;
+// Random topology WITHOUT fair peer selection: every row draws independently among the
+// other n-1 rows, so rows may be picked twice or never (the paper's comparison case).
+void unfair_table(const DrawStream &rng, int32_t n, int32_t *recv_from)
+{
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t pick = static_cast<int32_t>(rng.below(static_cast<uint32_t>(i), static_cast<uint32_t>(n - 1)));
+        recv_from[i] = pick + (pick >= i ? 1 : 0);      // skip the row itself
+    }
+}
+
 std::atomic<int32_t> g_tuning[kTuningKeys] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
 
 }  // namespace
@@ -94,7 +104,9 @@ int cx_topology_gen(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t
     if (!peers_host) return CX_ERR_NULL;
     if (n < 2 || n > CX_MAX_ROWS || S < 1 || R < 0 || round0 < 0) return CX_ERR_SHAPE;
     if (static_cast<int64_t>(round0) + R > INT32_MAX) return CX_ERR_SHAPE;
-    if (mode != 0 && mode != 1) return CX_ERR_UNSUPPORTED;
+    const bool same_for_all_segments = (mode & CX_TOPO_SAME_ALL_SEGMENTS) != 0;
+    mode &= ~CX_TOPO_SAME_ALL_SEGMENTS;
+    if (mode != CX_TOPO_FAIR && mode != CX_TOPO_DIRECTED_EXP && mode != CX_TOPO_UNFAIR) return CX_ERR_UNSUPPORTED;
 
     int32_t hops = 0;                       // number of distinct exponential hops
     while ((int64_t{1} << hops) < n) ++hops;
@@ -105,9 +117,13 @@ int cx_topology_gen(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t
         const int32_t t = round0 + r;
         for (int32_t s = 0; s < S; ++s) {
             int32_t *row = peers_host + (static_cast<int64_t>(r) * S + s) * n;
-            if (mode == 0) {
+            if (same_for_all_segments && s > 0) {
+                std::copy_n(peers_host + static_cast<int64_t>(r) * S * n, n, row);
+            } else if (mode == CX_TOPO_FAIR) {
                 fair_table(DrawStream(seed, static_cast<uint32_t>(t), static_cast<uint32_t>(s)),
                            n, row, pool);
+            } else if (mode == CX_TOPO_UNFAIR) {
+                unfair_table(DrawStream(seed, static_cast<uint32_t>(t), static_cast<uint32_t>(s)), n, row);
             } else {
                 const int32_t hop = static_cast<int32_t>((int64_t{1} << (t % hops)) % n);
                 for (int32_t i = 0; i < n; ++i) row[i] = i >= hop ? i - hop : i - hop + n;

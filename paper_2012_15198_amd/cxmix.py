@@ -22,6 +22,7 @@ CX_OK = 0
 STATUS = {0: "CX_OK", -1: "CX_ERR_NULL", -2: "CX_ERR_SHAPE", -3: "CX_ERR_SEGMENTS",
           -4: "CX_ERR_PEERS", -5: "CX_ERR_ALIGN", -6: "CX_ERR_ALIAS", -7: "CX_ERR_HIP",
           -8: "CX_ERR_UNSUPPORTED"}
+CX_TOPO_FAIR, CX_TOPO_DIRECTED_EXP, CX_TOPO_UNFAIR, CX_TOPO_SAME_ALL_SEGMENTS = 0, 1, 2, 16
 TUNE_SLICES, TUNE_WAVES, TUNE_NONTEMPORAL, TUNE_DEPTH = 0, 1, 2, 3
 TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE, TUNE_ORDERED = 4, 5, 6, 7, 8
 

@@ -123,6 +123,31 @@ def test_tables_that_are_not_permutations():
         assert same_bits(run_gossip(x, P, so, bad, False), O.gossip_mix(x, P, so, ref))
 
 
+def test_unfair_and_model_wise_topologies_out_of_place():
+    W, P, S, R = 12, 9001, 5, 4
+    x = WL.gen_matrix(W, P, 1.0, seed=27, ld=9004)
+    so = WL.equal_seg_off(P, S)
+    sod = dev(so)
+    for mode in (cx.CX_TOPO_UNFAIR, cx.CX_TOPO_FAIR | cx.CX_TOPO_SAME_ALL_SEGMENTS,
+                 cx.CX_TOPO_UNFAIR | cx.CX_TOPO_SAME_ALL_SEGMENTS):
+        tabs = cx.cx_topology_gen(27, W, S, 0, R, mode)
+        assert (tabs == O.topology(27, W, S, 0, R, mode)).all()
+        a, b = dev(x), torch.empty(W, 9004, device="cuda:0")
+        b[:, P:] = a[:, P:]
+        want = x
+        for r in range(R):
+            cx.cx_gossip_mix(a, b, P, sod, dev(tabs[r]))
+            a, b = b, a
+            want = O.gossip_mix(want, P, so, tabs[r])
+        torch.cuda.synchronize()
+        assert same_bits(host(a), want)
+        if mode & cx.CX_TOPO_SAME_ALL_SEGMENTS:      # one table for all segments = model-wise
+            one = x
+            for r in range(R):
+                one = O.gossip_mix(one, P, [0, P], tabs[r][:1])
+            assert same_bits(want, one)
+
+
 def test_deterministic_and_inplace_equals_pingpong_over_rounds():
     W, P, S, R = 16, 10007, 5, 6
     x = WL.gen_matrix(W, P, 1.0, seed=25, ld=10008)

@@ -1,0 +1,119 @@
+"""CPU tests of the comparison topologies (random without fair selection, one table for all
+segments) in the oracle and the library, and of the mixing-matrix analysis that checks the
+generators against Theorems 1 and 2 of the paper."""
+import math
+from collections import Counter
+
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2012_15198_amd import cxmix as cx
+from paper_2012_15198_amd import mixing_analysis as MA
+
+UNFAIR, SAME = 2, 16
+
+
+def test_unfair_table_by_hand_from_the_raw_draws():
+    for n in (2, 3, 7, 40):
+        for r in range(10):
+            key = O.key(5, r, 1)
+            want = []
+            for i in range(n):
+                others = [j for j in range(n) if j != i]
+                want.append(others[(O.draw(key, i) * (n - 1)) >> 64])
+            assert O.topology(5, n, 2, r, 1, UNFAIR)[0, 1].tolist() == want
+
+
+def test_unfair_draws_are_uniform_independent_and_allow_duplicates():
+    n, R = 5, 4000
+    t = O.topology(9, n, 4, 0, R, UNFAIR).reshape(-1, n)
+    assert ((t >= 0) & (t < n)).all() and (t != np.arange(n)).all()
+    for i in range(n):                       # each row uniform over the other n-1 rows
+        cnt = Counter(t[:, i].tolist())
+        exp = len(t) / (n - 1)
+        chi2 = sum((cnt.get(j, 0) - exp) ** 2 / exp for j in range(n) if j != i)
+        assert chi2 < 25.0, (i, chi2)
+    # n = 3: 8 equally likely tables, 2 of them are permutations -> 1/4
+    t3 = O.topology(9, 3, 1, 0, 20000, UNFAIR)[:, 0]
+    perms = np.mean([len(set(row)) == 3 for row in t3.tolist()])
+    assert abs(perms - 0.25) < 0.015
+    # pairs of rows are independent: joint frequency factorises (row 0 and row 1 at n = 3)
+    joint = Counter((a, b) for a, b, _ in t3.tolist())
+    assert all(abs(c / len(t3) - 0.25) < 0.015 for c in joint.values()) and len(joint) == 4
+
+
+def test_same_table_for_all_segments_flag():
+    for mode in (0, 2):
+        t = O.topology(3, 9, 5, 0, 6, mode | SAME)
+        assert (t == t[:, :1]).all()
+        assert (t[:, 0] == O.topology(3, 9, 5, 0, 6, mode)[:, 0]).all()
+        assert len({tuple(x) for x in t[:, 0].tolist()}) == 6      # still changes every round
+
+
+@pytest.mark.parametrize("mode", [2, 16, 17, 18])
+def test_library_modes_are_bit_exact_against_the_oracle(mode):
+    for n, S, R in [(2, 3, 4), (5, 4, 50), (32, 8, 10), (128, 2, 3), (1024, 1, 2)]:
+        assert (cx.cx_topology_gen(7, n, S, 2, R, mode) == O.topology(7, n, S, 2, R, mode)).all()
+    out = np.zeros((1, 1, 4), dtype=np.int32)
+    assert cx.lib().cx_topology_gen(0, 4, 1, 0, 1, 3, out.ctypes.data) == -8
+    assert cx.lib().cx_topology_gen(0, 4, 1, 0, 1, 32, out.ctypes.data) == -8
+
+
+def test_unfair_mixing_on_the_oracle_breaks_mean_conservation():
+    # Section 3.2: without fair selection some workers are not received from at all, so the
+    # column mean drifts (row-stochastic mixing), whereas the fair topology keeps it.
+    from paper_2012_15198_amd import workloads as WL
+    W, P = 8, 200
+    x0 = WL.gen_matrix(W, P, 1.0, 4)
+    for mode, keeps in [(0, True), (UNFAIR, False)]:
+        x = x0
+        for r in range(6):
+            x = O.gossip_mix(x, P, [0, P], O.topology(4, W, 1, r, 1, mode)[0])
+        drift = np.abs(x.astype(np.float64).mean(0) - x0.astype(np.float64).mean(0)).max()
+        assert (drift < 1e-6) == keeps
+
+
+# ------------------------------------------------------------------ Theorems 1 and 2
+def test_fair_products_converge_to_allreduce_theorem_1():
+    r = MA.analyse(seed=1, n=16, rounds=120, mode="fair")
+    assert r["imbalance"][-1] < 1e-20 and r["lambda2"][-1] < 1e-8
+    assert all(b <= a * (1 + 1e-9) + 1e-18 for a, b in zip(r["imbalance"], r["imbalance"][1:]))
+    for prod in MA.running_products(cx.cx_topology_gen(1, 16, 1, 0, 5)[:, 0]):
+        assert np.allclose(prod.sum(0), 1) and np.allclose(prod.sum(1), 1)   # doubly stochastic
+
+
+def test_unfair_products_become_rank_one_but_stay_imbalanced_theorem_2():
+    finals = []
+    for seed in range(8):
+        r = MA.analyse(seed=seed, n=16, rounds=200, mode="unfair")
+        assert r["lambda2"][-1] < 1e-6                      # identical rows: rank one
+        finals.append(r["imbalance"][-1])
+    assert min(finals) > 1e-5                               # but not the uniform matrix
+    prods = list(MA.running_products(cx.cx_topology_gen(0, 16, 1, 0, 200, 2)[:, 0]))
+    last = prods[-1]
+    assert np.allclose(last, last[0]) and np.allclose(last.sum(1), 1)
+    assert np.abs(last.sum(0) - 1).max() > 1e-3             # columns do not sum to one
+
+
+def test_directed_exponential_reaches_exact_average_in_log2_n_rounds():
+    r = MA.analyse(seed=0, n=16, rounds=4, mode="directed_exponential")
+    assert r["imbalance"][-1] < 1e-30 and r["imbalance"][2] > 1e-6
+    # one round of either topology is (I + permutation)/2: the same imbalance factor
+    fair = MA.analyse(3, 16, 1, "fair")["imbalance"]
+    assert fair[0] == pytest.approx(r["imbalance"][0])
+    # Section 3.2's claim about the second eigenvalue of the product: in the early rounds
+    # (before the exponential graph completes its log2(n) hops) the fair random topology has
+    # the lower one on average
+    de = MA.analyse(0, 16, 3, "directed_exponential")["lambda2"]
+    fr = np.mean([MA.analyse(s, 16, 3, "fair")["lambda2"] for s in range(40)], axis=0)
+    assert fr[1] < de[1] and fr[2] < de[2]
+
+
+def test_mixing_matrix_matches_one_oracle_round():
+    from paper_2012_15198_amd import workloads as WL
+    W, P = 7, 25
+    x = WL.gen_matrix(W, P, 1.0, 3)
+    d = O.topology(3, W, 1, 0, 1, 2)[0, 0]
+    ref = MA.mixing_matrix(d) @ x.astype(np.float64)
+    assert np.abs(O.gossip_mix(x, P, [0, P], [d]) - ref).max() < 1e-6
