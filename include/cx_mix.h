@@ -201,6 +201,17 @@ int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, fl
                           const int32_t *leader_peers_dev, uint32_t flags, void *stream);
 
 /* ------------------------------------------------------------------------------------
+ * cx_gossip_mix_bf16 -- cx_gossip_mix on bfloat16 rows (the paper trains in mixed precision,
+ * Section 4.1 / Table 1): x is uint16 [W][ld] holding bfloat16 bit patterns, ld % 8 == 0,
+ *     x_out[i][c] = bf16_rne((float(x_in[i][c]) + float(x_in[peers[s][i]][c])) * 0.5f),
+ * fp32 arithmetic, one rounding to bfloat16 (nearest even; NaN stays a quiet NaN).  Moves
+ * 4 bytes per worker-parameter.  Everything else as cx_gossip_mix.
+ */
+int cx_gossip_mix_bf16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int64_t P,
+                       int32_t S, const int64_t *seg_off_dev, const int32_t *peers_dev,
+                       uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method).
  * cx_copy_baseline: dst[i] = src[i] for n floats (n % 4 == 0, 16-byte aligned) with the
  * same load/store instructions as the mixing kernels; the practical HBM ceiling and the

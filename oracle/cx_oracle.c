@@ -176,6 +176,45 @@ int oracle_gossip_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, in
 }
 
 /* ------------------------------------------------------------------------- */
+/* The same averaging on bfloat16 rows (the paper trains in mixed precision): */
+/* widen both values to fp32, add, halve, round once to bfloat16 (nearest,    */
+/* ties to even).  x holds bfloat16 bit patterns.                             */
+/* ------------------------------------------------------------------------- */
+float oracle_bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+uint16_t oracle_f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   /* NaN stays NaN */
+    uint32_t kept_lsb = (u >> 16) & 1u;
+    u += 0x7fffu + kept_lsb;          /* below half rounds down, above up, a tie to the even */
+    return (uint16_t)(u >> 16);
+}
+
+int oracle_gossip_mix_bf16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int64_t P,
+                           int32_t S, const int64_t *seg_off, const int32_t *peers)
+{
+    (void)P;
+    for (int32_t s = 0; s < S; ++s)
+        for (int32_t i = 0; i < W; ++i) {
+            int32_t j = peers[(int64_t)s * W + i];
+            for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+                float a = oracle_bf16_to_f32(x_in[i * ld + c]);
+                float b = oracle_bf16_to_f32(x_in[j * ld + c]);
+                x_out[i * ld + c] = oracle_f32_to_bf16((a + b) * 0.5f);
+            }
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Hierarchical variant (Section 3.3): (1) reduce inside each group of G      */
 /* consecutive rows to the group mean held by the leader, (2) the L = W/G     */
 /* leaders gossip segment-wise, (3) the leader's result is broadcast to its   */

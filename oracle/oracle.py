@@ -22,7 +22,8 @@ _lib = None
 __all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topology",
            "gossip_mix", "hier_mix_f64", "hier_mix_f32", "sgd_fused_mix_f64",
            "sgd_fused_mix_f32", "pushsum_mix_f64", "pushsum_mix_f32",
-           "hier_sgd_fused_mix_f64", "hier_sgd_fused_mix_f32"]
+           "hier_sgd_fused_mix_f64", "hier_sgd_fused_mix_f32", "gossip_mix_bf16", "f32_to_bf16",
+           "bf16_to_f32"]
 
 
 def build_oracle(force: bool = False) -> str:
@@ -51,6 +52,11 @@ def _L():
         lib.oracle_fair_draw.argtypes = [u64, i32, vp]
         lib.oracle_topology.argtypes = [u64, i32, i32, i32, i32, i32, vp]
         lib.oracle_gossip_mix.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp]
+        lib.oracle_gossip_mix_bf16.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp]
+        lib.oracle_f32_to_bf16.restype = ctypes.c_uint16
+        lib.oracle_f32_to_bf16.argtypes = [f32]
+        lib.oracle_bf16_to_f32.restype = f32
+        lib.oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
         lib.oracle_hier_mix_f64.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_hier_mix_f32.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_sgd_fused_mix_f64.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32,
@@ -235,3 +241,27 @@ def hier_sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, G, seg_off, leader_peers):
 def hier_sgd_fused_mix_f32(x, v, g, lr, mu, wd, P, G, seg_off, leader_peers):
     return _hier_fused(_L().oracle_hier_sgd_fused_mix_f32, np.float32, x, v, g, lr, mu, wd, P, G,
                        seg_off, leader_peers)
+
+
+def f32_to_bf16(a) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) of float32 values, round-to-nearest-even."""
+    a = np.asarray(a, dtype=np.float32)
+    fn = _L().oracle_f32_to_bf16
+    return np.array([fn(float(v)) for v in a.ravel()], dtype=np.uint16).reshape(a.shape)
+
+
+def bf16_to_f32(h) -> np.ndarray:
+    h = np.asarray(h, dtype=np.uint16)
+    return (h.astype(np.uint32) << 16).view(np.float32)
+
+
+def gossip_mix_bf16(x, P, seg_off, peers) -> np.ndarray:
+    """x: uint16 [W][ld] of bfloat16 bit patterns; returns the mixed patterns."""
+    x = _mat(x, dtype=np.uint16)
+    W, ld = x.shape
+    so = _seg(seg_off, P)
+    S = len(so) - 1
+    pe = _peers(peers, S, W)
+    out = x.copy()
+    _check(_L().oracle_gossip_mix_bf16(_p(x), _p(out), ld, W, P, S, _p(so), _p(pe)), "gossip_mix_bf16")
+    return out

@@ -62,6 +62,7 @@ constexpr int kMaxWavesPerBlock = 8;
 
 template <int U>
 struct Tile {
+    static constexpr int kN = U;
     f4 v[U];
 };
 
@@ -148,6 +149,8 @@ __device__ __forceinline__ Tile<U> tree_sum(const Tile<U> *r)
 // Plain gossip (G == 1) and hierarchical mode (a gossiping row = a group of G rows).
 template <int G>
 struct MeanOp {
+    static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
+    template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = G;
     template <int U> struct Raw { Tile<U> r[G]; };
     const float *xin;
@@ -184,6 +187,8 @@ struct MeanOp {
 
 // Momentum-SGD applied as the row arrives; the walk then mixes the updated rows.
 struct FusedOp {
+    static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
+    template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = 3;
     template <int U> struct Raw { Tile<U> x, v, g; };
     const float *xin;
@@ -227,6 +232,8 @@ struct FusedOp {
 // and momentum, and hands the updated leader parameters to the walk; storing broadcasts.
 template <int G>
 struct HierFusedOp {
+    static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
+    template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = G + 2;
     template <int U> struct Raw { Tile<U> g[G], x, v; };
     const float *xin;
@@ -269,8 +276,105 @@ struct HierFusedOp {
     }
 };
 
+// ---------------------------------------------------------------------------------
+// bfloat16 rows (8 columns per 16-byte slice), averaged in fp32:
+//     out = bf16_rne((float(a) + float(b)) * 0.5f)
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(unsigned h) { return __uint_as_float(h << 16); }
+
+// round-to-nearest-even; a NaN stays a (quiet) NaN
+__device__ __forceinline__ unsigned float_to_bf16_bits(float f)
+{
+    const unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int U, bool FULL, bool NT>
+__device__ __forceinline__ void tile_load16(const uint16_t *p, const unsigned (&mask)[U], Tile<U> &raw)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if constexpr (FULL) {
+            const f4 *q = reinterpret_cast<const f4 *>(p + u * (kWave * 8));
+            raw.v[u] = NT ? __builtin_nontemporal_load(q) : *q;
+        } else {
+            u4 w = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if ((mask[u] >> e) & 1u) w[e >> 1] |= static_cast<unsigned>(p[u * (kWave * 8) + e]) << (16 * (e & 1));
+            raw.v[u] = __builtin_bit_cast(f4, w);
+        }
+    }
+}
+
+template <int U, bool FULL, bool NT>
+__device__ __forceinline__ void tile_store16(uint16_t *p, const unsigned (&mask)[U], const Tile<U> &raw)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if constexpr (FULL) {
+            f4 *q = reinterpret_cast<f4 *>(p + u * (kWave * 8));
+            if (NT) __builtin_nontemporal_store(raw.v[u], q); else *q = raw.v[u];
+        } else {
+            const u4 w = __builtin_bit_cast(u4, raw.v[u]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if ((mask[u] >> e) & 1u)
+                    p[u * (kWave * 8) + e] = static_cast<uint16_t>(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+}
+
+struct Bf16Op {
+    static constexpr int kElems = 8;                       // bf16 columns per 16-byte slice
+    template <int U> using Work = Tile<2 * U>;             // 8 fp32 values per slice
+    static constexpr int kRawPerSlice = 1;
+    template <int U> struct Raw { Tile<U> x; };            // packed bf16 pairs, as loaded
+    const uint16_t *xin;
+    uint16_t *xout;
+    int64_t ld;
+
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
+    {
+        tile_load16<U, FULL, NT>(xin + static_cast<int64_t>(row) * ld + off, mask, raw.x);
+    }
+    template <int U, bool FULL, bool NT, bool COMMIT = true>
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
+    {
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const u4 w = __builtin_bit_cast(u4, raw.x.v[u]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                t.v[2 * u + (e >> 2)][e & 3] = bf16_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+        }
+    }
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
+    {
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        Tile<U> packed;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            u4 w = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                w[e >> 1] |= float_to_bf16_bits(t.v[2 * u + (e >> 2)][e & 3]) << (16 * (e & 1));
+            packed.v[u] = __builtin_bit_cast(f4, w);
+        }
+        tile_store16<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
+    }
+};
+
 // Push-sum: plain rows, optional de-biased copy z = x' / w'.
 struct PushOp {
+    static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
+    template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = 1;
     template <int U> struct Raw { Tile<U> x; };
     const float *xin;
@@ -360,20 +464,21 @@ template <class Op, int U, int D, bool FULL, bool NT, bool SYNC = false>
 __device__ __forceinline__ void walk(const Op &op, const int *sched, int n, bool skip_mix,
                                      int64_t off, const unsigned (&mask)[U])
 {
+    using WorkT = typename Op::template Work<U>;
     typename Op::template Raw<U> slot[D];
 #pragma unroll
     for (int j = 0; j < D; ++j)
         if (j < n) op.template issue<U, FULL, NT>(uniform(sched[j]) & kRowMask, off, mask, slot[j]);
 
     int e = uniform(sched[0]);
-    Tile<U> cur;
+    WorkT cur;
     op.template finish<U, FULL, NT>(e & kRowMask, off, mask, slot[0], cur);
     if (D < n) op.template issue<U, FULL, NT>(uniform(sched[D]) & kRowMask, off, mask, slot[0]);
     if (skip_mix) {                       // a single gossiping row: nothing to average with
         op.template store<U, FULL, NT>(e & kRowMask, off, mask, cur);
         return;
     }
-    Tile<U> first = cur;
+    WorkT first = cur;
     for (int base = 0; base < n; base += D) {
         static_for<0, D>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
@@ -381,7 +486,7 @@ __device__ __forceinline__ void walk(const Op &op, const int *sched, int n, bool
             const int k = base + j;
             if (k < n) {
                 if constexpr (SYNC) __syncthreads();   // the workgroup visits each row together
-                Tile<U> nx;
+                WorkT nx;
                 int e1 = 0;
                 if (k + 1 < n) {          // row of step k+1 arrives; its slot is refilled at once
                     e1 = uniform(sched[k + 1]);
@@ -391,9 +496,9 @@ __device__ __forceinline__ void walk(const Op &op, const int *sched, int n, bool
                                                        slot[kNextSlot]);
                 }
                 const bool last = (e & kLastBit) != 0;      // row k closes its cycle
-                Tile<U> out;
+                WorkT out;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
+                for (int u = 0; u < WorkT::kN; ++u) {
                     const f4 partner = last ? first.v[u] : nx.v[u];
                     out.v[u] = (cur.v[u] + partner) * 0.5f;
                 }
@@ -416,7 +521,8 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
     const int wave = uniform(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
     const int64_t tile = static_cast<int64_t>(blockIdx.x) * nwaves + wave;
-    constexpr int kTileCols = 256 * U;
+    constexpr int kSliceCols = Op::kElems;            // columns in one 16-byte slice
+    constexpr int kTileCols = kWave * kSliceCols * U;
 
     if (lockstep) {
         // Workgroup-uniform fast path: the whole super-tile of the workgroup lies inside one
@@ -438,8 +544,8 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
             __syncthreads();
             unsigned mask[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) mask[u] = 0xFu;
-            walk<Op, U, D, true, NT, true>(op, sched, n, skip_mix != 0, tile * kTileCols + 4 * lane, mask);
+            for (int u = 0; u < U; ++u) mask[u] = (1u << kSliceCols) - 1u;
+            walk<Op, U, D, true, NT, true>(op, sched, n, skip_mix != 0, tile * kTileCols + kSliceCols * lane, mask);
             return;
         }
     }
@@ -449,7 +555,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
 
     const int64_t c0 = tile * kTileCols;
     const int64_t c1 = (c0 + kTileCols < P) ? c0 + kTileCols : P;
-    const int64_t off = c0 + 4 * lane;
+    const int64_t off = c0 + kSliceCols * lane;
 
     // segment that holds column c0: number of interior boundaries <= c0
     int lo = 1, hi = S;
@@ -470,15 +576,15 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
         unsigned mask[U];
         if (b == c0 && e == c0 + kTileCols) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) mask[u] = 0xFu;
+            for (int u = 0; u < U; ++u) mask[u] = (1u << kSliceCols) - 1u;
             walk<Op, U, D, true, NT>(op, sched, n, skip_mix != 0, off, mask);
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 mask[u] = 0;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int64_t c = off + u * 256 + q;
+                for (int q = 0; q < kSliceCols; ++q) {
+                    const int64_t c = off + u * (kWave * kSliceCols) + q;
                     if (c >= b && c < e) mask[u] |= 1u << q;
                 }
             }
@@ -566,11 +672,12 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
         if (static_cast<unsigned>(row) >= static_cast<unsigned>(n)) row = blockIdx.y;
     }
 
-    constexpr int kTileCols = 256 * U;
+    constexpr int kSliceCols = Op::kElems;
+    constexpr int kTileCols = kWave * kSliceCols * U;
     const int64_t c0 = (chunk * nwaves + wave) * kTileCols;
     if (c0 >= P) return;
     const int64_t c1 = (c0 + kTileCols < P) ? c0 + kTileCols : P;
-    const int64_t off = c0 + 4 * lane;
+    const int64_t off = c0 + kSliceCols * lane;
     const bool whole = c0 + kTileCols <= P;      // the tile does not hang over the row end
 
     // The row's own data does not depend on the segment: put its loads in flight first and
@@ -578,7 +685,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     typename Op::template Raw<U> mine;
     unsigned full_mask[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) full_mask[u] = 0xFu;
+    for (int u = 0; u < U; ++u) full_mask[u] = (1u << kSliceCols) - 1u;
     if (whole) op.template issue<U, true, false>(row, off, full_mask, mine);
 
     // Segment and partner lookup.  With up to 63 segments one vector load brings the whole
@@ -629,12 +736,12 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
         auto mix_and_store = [&](auto full_c, const unsigned (&m)[U]) {
             constexpr bool FULL = decltype(full_c)::value;
             constexpr bool kOneAtATime = Op::kRawPerSlice * U >= 16;
-            Tile<U> a, out;
+            typename Op::template Work<U> a, out;
             if (skip_mix) {
                 op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
                 out = a;
             } else {
-                Tile<U> c;
+                typename Op::template Work<U> c;
                 if constexpr (kOneAtATime) {
                     op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
                     op.template issue<U, FULL, false>(peer, off, m, mine);
@@ -646,7 +753,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
                     op.template finish<U, FULL, NT, false>(peer, off, m, theirs, c);
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
+                for (int u = 0; u < Op::template Work<U>::kN; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
             }
             op.template store<U, FULL, NT>(row, off, m, out);
         };
@@ -661,8 +768,8 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
         for (int u = 0; u < U; ++u) {
             mask[u] = 0;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int64_t c = off + u * 256 + q;
+            for (int q = 0; q < kSliceCols; ++q) {
+                const int64_t c = off + u * (kWave * kSliceCols) + q;
                 if (c >= sb && c < se) mask[u] |= 1u << q;
             }
         }
@@ -683,13 +790,13 @@ Launch pick_launch(int default_u, int default_d)
     Launch l;
     l.U = cx_get_tuning(0);
     if (l.U != 1 && l.U != 2 && l.U != 4) l.U = default_u;
+    l.lockstep = cx_get_tuning(4) == 0 ? 0 : 1;
     l.waves = cx_get_tuning(1);
-    if (l.waves < 1 || l.waves > kMaxWavesPerBlock) l.waves = 4;
+    if (l.waves < 1 || l.waves > kMaxWavesPerBlock) l.waves = l.lockstep ? 8 : 4;
     l.nt = cx_get_tuning(2);
     if (l.nt != 0 && l.nt != 1) l.nt = 1;
     l.D = cx_get_tuning(3);
     if (l.D != 2 && l.D != 4 && l.D != 8) l.D = default_d;
-    l.lockstep = cx_get_tuning(4) == 1 ? 1 : 0;
     return l;
 }
 
@@ -734,7 +841,7 @@ bool try_launch(const Op &op, const Launch &l, const MixArgs &a)
     if constexpr (!fits<Op, U, D>()) {
         return false;
     } else {
-        const int64_t tile_cols = 256 * U;
+        const int64_t tile_cols = static_cast<int64_t>(kWave) * Op::kElems * U;
         const int64_t ntiles = (a.P + tile_cols - 1) / tile_cols;
         int waves = l.waves;
         while (waves > 1 && sizeof(int) * 2 * static_cast<size_t>(a.n) * waves > 48 * 1024) --waves;
@@ -765,13 +872,13 @@ int order_slot_for(hipStream_t stream)
     return used++;
 }
 
-// Out-of-place launch: one workgroup per (gossiping row, chunk of waves * 256 * U columns).
+// Out-of-place launch: one workgroup per (gossiping row, chunk of waves * 64 * U slices).
 template <class Op, int U>
 bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd_aware, const MixArgs &a,
                 int *status)
 {
     if (want_u != U) return false;
-    const int64_t chunk_cols = static_cast<int64_t>(256) * U * waves;
+    const int64_t chunk_cols = static_cast<int64_t>(kWave) * Op::kElems * U * waves;
     const int64_t nchunks = (a.P + chunk_cols - 1) / chunk_cols;
     const int nxcd = xcd_aware ? 8 : 1;
     bool ordered = cx_get_tuning(8) != 0 && a.n > 1 && a.S <= 4096;
@@ -782,7 +889,7 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
         // ordered rows: a row visit of 512 KB per XCD (measured optimum on MI355X: shorter
         // visits lose DRAM row locality, longer ones push the previous visit out of L2);
         // natural row order: the whole cluster (all rows) should fit one XCD's 4 MB L2
-        const int64_t row_bytes = chunk_cols * 4 * a.rows_per_gossip_row;
+        const int64_t row_bytes = chunk_cols * (16 / Op::kElems) * a.rows_per_gossip_row;
         cl = ordered ? (512 << 10) / row_bytes : (4 << 20) / (row_bytes * a.n);
         if (cl < 1) cl = 1;
     }
@@ -854,14 +961,14 @@ int launch_mix(const Op &op, const MixArgs &a)
     return hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
 }
 
-int check_matrix_args(const void *x_in, const void *x_out, int64_t ld, int64_t rows, int64_t P,
-                      int32_t S, uint32_t flags)
+[[maybe_unused]] int check_matrix_args(const void *x_in, const void *x_out, int64_t ld, int64_t rows,
+                                       int64_t P, int32_t S, uint32_t flags, int elem_bytes = 4)
 {
     if (!x_in || !x_out) return CX_ERR_NULL;
     if (S < 1 || P < 1 || ld < P || rows < 1) return CX_ERR_SHAPE;
     if (rows > (INT64_MAX / 4) / ld) return CX_ERR_SHAPE;
-    if ((ld & 3) != 0 || misaligned(x_in) || misaligned(x_out)) return CX_ERR_ALIGN;
-    if (partial_overlap(x_in, x_out, static_cast<uint64_t>(rows) * ld * 4u)) return CX_ERR_ALIAS;
+    if (ld % (16 / elem_bytes) != 0 || misaligned(x_in) || misaligned(x_out)) return CX_ERR_ALIGN;
+    if (partial_overlap(x_in, x_out, static_cast<uint64_t>(rows) * ld * elem_bytes)) return CX_ERR_ALIAS;
     if (flags != 0) return CX_ERR_UNSUPPORTED;
     return CX_OK;
 }

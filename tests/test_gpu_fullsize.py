@@ -95,6 +95,28 @@ def test_c2_whole_matrix_three_rounds_and_sampled_all_rounds():
     free(a, b, c, xd)
 
 
+def test_c2_bf16_rows_sampled_all_rounds():
+    wl = WL.WORKLOADS["C2"]
+    so = WL.equal_seg_off(wl.P, wl.S)
+    ld = padded(wl.P)
+    tabs = cx.cx_topology_gen(wl.seed, wl.W, wl.S, 0, wl.rounds)
+    xd = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld).to(torch.bfloat16)
+    cols, sso, cold = sample(wl, so)
+    grab = lambda t: host(t.view(torch.int16).index_select(1, cold)).view(np.uint16)
+    sub = grab(xd)
+    a, b, c = xd, torch.empty_like(xd), xd.clone()
+    sod = dev(so)
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        cx.cx_gossip_mix_bf16(a, b, wl.P, sod, t)
+        a, b = b, a
+        cx.cx_gossip_mix_bf16(c, c, wl.P, sod, t)
+        sub = O.gossip_mix_bf16(sub, len(cols), sso, tabs[r])
+    torch.cuda.synchronize()
+    assert (grab(a) == sub).all() and (grab(c) == sub).all()
+    free(a, b, c, xd)
+
+
 def hier_bound(xsub, G, ysub64, pe, sso):
     W, n = xsub.shape
     L = W // G

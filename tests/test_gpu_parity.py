@@ -189,6 +189,50 @@ def test_out_of_place_calls_on_more_streams_than_order_table_slots():
         assert same_bits(host(b)[:, :P], O.gossip_mix(x, P, so, t)[:, :P])
 
 
+# ----------------------------------------------------------------------- bfloat16 rows
+def same_bf16(a, b):
+    isnan = lambda h: ((h & 0x7F80) == 0x7F80) & ((h & 0x007F) != 0)
+    return bool(((a == b) | (isnan(a) & isnan(b))).all())
+
+
+@pytest.mark.parametrize("W,P,ld,S", [(2, 1, 8, 1), (2, 13, 16, 2), (3, 2048, 2048, 1), (8, 9001, 9008, 4),
+                                      (5, 8195, 8320, 7), (33, 5003, 5008, 8), (64, 3000, 3000, 5)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_gossip_bf16_bit_exact(W, P, ld, S, inplace):
+    xb = O.f32_to_bf16(WL.gen_matrix(W, P, 1.0, seed=W * 7 + P, ld=ld))
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(71, W, S, 0, 1)[0]
+    want = O.gossip_mix_bf16(xb, P, so, pe)
+    xd = dev(xb.view(np.int16))
+    out = xd if inplace else xd.clone()
+    cx.cx_gossip_mix_bf16(xd, out, P, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    assert same_bf16(host(out).view(np.uint16), want)
+
+
+@pytest.mark.parametrize("tuning", ALL_TUNINGS)
+def test_gossip_bf16_rounds_edge_values_every_launch_shape(tuning):
+    W, P, ld, S, R = 10, 12345, 12352, 6, 3
+    x = np.stack([WL.edge_values(ld, seed=80 + i) for i in range(W)])
+    x[~np.isfinite(x)] = 1.0
+    xb = O.f32_to_bf16(x)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(72, W, S, 0, R)
+    want = xb
+    with np.errstate(all="ignore"):
+        for r in range(R):
+            want = O.gossip_mix_bf16(want, P, so, tabs[r])
+    with Tuning(*tuning):
+        a = dev(xb.view(np.int16))
+        y0, y1 = dev(xb.view(np.int16)), dev(xb.view(np.int16))
+        for r in range(R):
+            cx.cx_gossip_mix_bf16(a, a, P, dev(so), dev(tabs[r]))
+            cx.cx_gossip_mix_bf16(y0, y1, P, dev(so), dev(tabs[r]))
+            y0, y1 = y1, y0
+        torch.cuda.synchronize()
+    assert same_bf16(host(a).view(np.uint16), want) and same_bf16(host(y0).view(np.uint16), want)
+
+
 # ------------------------------------------------------------------------ hierarchical
 def hier_tol(x, G, P, y64, pe, so):
     """1e-6 relative to max(|ref|, mean |x| over the rows that enter the result)."""

@@ -375,3 +375,40 @@ def test_hier_sgd_equal_gradients_and_lr0_reduce_to_known_cases():
     junk[1::G] = 1e9
     xj, vj = O.hier_sgd_fused_mix_f32(junk, v, g, 0.1, 0.9, 1e-4, P, G, so, pe)
     assert (xj == xo).all() and (vj == vo).all()
+
+
+# ------------------------------------------------------------------------- bfloat16 rows
+def test_bf16_rounding_by_hand_and_against_the_library_conversion():
+    import torch
+    # 1 + 2^-8 is a tie between 1.0 (even) and 1 + 2^-7: goes down; 1 + 3*2^-8 ties up to even
+    assert O.f32_to_bf16([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8]).tolist() == \
+        [0x3F80, 0x3F80, 0x3F81, 0x3F82]
+    assert O.f32_to_bf16([-2.5, 0.0, -0.0, np.inf, 3.3895314e38]).tolist() == [0xC020, 0, 0x8000, 0x7F80, 0x7F7F]
+    assert O.f32_to_bf16([3.4e38]).tolist() == [0x7F80]          # rounds up to infinity
+    vals = np.concatenate([WL.edge_values(4000, 3), WL.gen_matrix(1, 20000, 1.0, 3)[0],
+                           np.float32(2.0) ** np.arange(-140, 128, dtype=np.float32)])
+    vals = vals[~np.isnan(vals)]
+    ref = torch.from_numpy(vals).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert (O.f32_to_bf16(vals) == ref).all()
+    back = torch.from_numpy(ref.view(np.int16)).view(torch.bfloat16).float().numpy()
+    assert (O.bf16_to_f32(ref).view(np.uint32) == back.view(np.uint32)).all()
+    assert (O.f32_to_bf16([np.nan]) & 0x7FC0 == 0x7FC0).all()
+
+
+def test_bf16_mix_hand_case_and_agreement_with_the_fp32_mix():
+    # 1.0 and 1.0078125 (adjacent bf16): mean 1.00390625 is a tie -> even mantissa (1.0)
+    x = O.f32_to_bf16([[1.0, 3.0], [1.0078125, -1.0]])
+    y = O.gossip_mix_bf16(x, 2, [0, 2], [[1, 0]])
+    assert O.bf16_to_f32(y).tolist() == [[1.0, 1.0], [1.0, 1.0]]
+    W, P, S = 6, 300, 3
+    xf = WL.gen_matrix(W, P, 1.0, 30)
+    xb = O.f32_to_bf16(xf)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(30, W, S, 0, 1)[0]
+    yb = O.gossip_mix_bf16(xb, P, so, pe)
+    # equals the fp32 oracle on the widened inputs followed by one rounding
+    want = O.f32_to_bf16(O.gossip_mix(O.bf16_to_f32(xb), P, so, pe))
+    assert (yb == want).all()
+    # identical rows stay fixed; the column mean moves by at most half a bf16 ulp per round
+    same = np.tile(xb[:1], (W, 1))
+    assert (O.gossip_mix_bf16(same, P, so, pe) == same).all()
