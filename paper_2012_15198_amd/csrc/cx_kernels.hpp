@@ -282,14 +282,6 @@ struct HierFusedOp {
 // ---------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_float(unsigned h) { return __uint_as_float(h << 16); }
 
-// round-to-nearest-even; a NaN stays a (quiet) NaN
-__device__ __forceinline__ unsigned float_to_bf16_bits(float f)
-{
-    const unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
 template <int U, bool FULL, bool NT>
 __device__ __forceinline__ void tile_load16(const uint16_t *p, const unsigned (&mask)[U], Tile<U> &raw)
 {
@@ -358,13 +350,18 @@ struct Bf16Op {
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
     {
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 b2 __attribute__((ext_vector_type(2)));
         Tile<U> packed;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            u4 w = {0u, 0u, 0u, 0u};
+            u4 w;
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                w[e >> 1] |= float_to_bf16_bits(t.v[2 * u + (e >> 2)][e & 3]) << (16 * (e & 1));
+            for (int pair = 0; pair < 4; ++pair) {
+                // two fp32 -> one packed bf16 pair, round-to-nearest-even in hardware
+                const f2 two = {t.v[2 * u + (pair >> 1)][2 * (pair & 1)], t.v[2 * u + (pair >> 1)][2 * (pair & 1) + 1]};
+                w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
+            }
             packed.v[u] = __builtin_bit_cast(f4, w);
         }
         tile_store16<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
@@ -886,11 +883,12 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     if (slot < 0) ordered = false;
     int64_t cl = cl_req;
     if (cl < 1) {
-        // ordered rows: a row visit of 512 KB per XCD (measured optimum on MI355X: shorter
-        // visits lose DRAM row locality, longer ones push the previous visit out of L2);
+        // ordered rows: a row visit of 512 KB per XCD, 256 KB for 16-bit rows (measured optima
+        // on MI355X: shorter visits lose DRAM row locality, longer ones push the previous visit
+        // out of L2);
         // natural row order: the whole cluster (all rows) should fit one XCD's 4 MB L2
         const int64_t row_bytes = chunk_cols * (16 / Op::kElems) * a.rows_per_gossip_row;
-        cl = ordered ? (512 << 10) / row_bytes : (4 << 20) / (row_bytes * a.n);
+        cl = ordered ? (Op::kElems == 8 ? (256 << 10) : (512 << 10)) / row_bytes : (4 << 20) / (row_bytes * a.n);
         if (cl < 1) cl = 1;
     }
     if (ordered) {                                // the order table must fit its slot
