@@ -148,6 +148,46 @@ def test_unfair_and_model_wise_topologies_out_of_place():
             assert same_bits(want, one)
 
 
+def test_rounds_captured_in_a_hip_graph_replay_like_eager():
+    """The calls only enqueue kernels (no memset, no allocation), so a whole schedule of rounds
+    can be captured once and replayed; every replay must equal the eager result."""
+    W, P, S, R = 16, 30011, 4, 4
+    x = WL.gen_matrix(W, P, 1.0, seed=28, ld=30016)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(28, W, S, 0, R)
+    sod, tds = dev(so), [dev(t) for t in tabs]
+    want = x
+    for r in range(R):
+        want = O.gossip_mix(want, P, so, tabs[r])
+    a, b = dev(x), dev(x)
+    c = dev(x)
+    x0 = dev(x)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):              # warm up on the capture stream
+        cx.cx_gossip_mix(a, b, P, sod, tds[0], stream=side)
+        cx.cx_gossip_mix(c, c, P, sod, tds[0], stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for r in range(R):                     # R even: the result lands in `a` again
+            cx.cx_gossip_mix(a, b, P, sod, tds[r])
+            a, b = b, a
+            cx.cx_gossip_mix(c, c, P, sod, tds[r])
+    for replay in range(3):
+        a.copy_(x0)
+        c.copy_(x0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert same_bits(host(a), want) and same_bits(host(c), want), replay
+        # eager work between replays
+        cx.cx_gossip_mix(x0, b, P, sod, tds[replay])
+        torch.cuda.synchronize()
+        assert same_bits(host(b), O.gossip_mix(x, P, so, tabs[replay]))
+
+
 def test_deterministic_and_inplace_equals_pingpong_over_rounds():
     W, P, S, R = 16, 10007, 5, 6
     x = WL.gen_matrix(W, P, 1.0, seed=25, ld=10008)

@@ -41,6 +41,17 @@ def test_topology_is_bit_exact_against_the_oracle(n, S, R, seed):
         cx.cx_check_peers(tab)
 
 
+def test_topology_matches_the_stored_oracle_tables(golden_dir):
+    rows = [l for l in open(os.path.join(golden_dir, "topology_seed2_n8.txt")) if not l.startswith("#")]
+    assert len(rows) >= 20
+    for line in rows:
+        head, tail = line.split(":")
+        seed, n, S, rnd, seg, mode = map(int, head.split())
+        want = list(map(int, tail.split()))
+        got = cx.cx_topology_gen(seed, n, S, rnd, 1, mode)[0, seg].tolist()
+        assert got == want, line
+
+
 def test_topology_argument_errors():
     out = np.zeros((1, 1, 4), dtype=np.int32)
     L = cx.lib()
