@@ -6,8 +6,9 @@
 //
 // Mixing is independent per column and every element has to be read once and written once
 // (8 B per worker-parameter; 20 B with the fused optimizer), so the whole path is bound by
-// HBM bandwidth.  A lane always handles 16-byte column slices (4 fp32), a wavefront 1 KB of
-// contiguous columns per memory instruction.  Two kernels serve the same arithmetic:
+// HBM bandwidth.  A lane always handles 16-byte column slices (4 fp32 or 8 bfloat16), a
+// wavefront 1 KB of contiguous columns per memory instruction.  Two kernels serve the same
+// arithmetic:
 //
 //  gather_kernel (output buffer != input buffer) -- the fast one.
 //   * One short-lived workgroup per (gossiping row, column chunk): it loads the row's chunk
@@ -22,7 +23,7 @@
 //     device-resident peer table into library-owned device memory (no allocation).
 //
 //  mix_kernel (in place capable) -- the column-owner cycle walk.
-//   * A wavefront owns a tile of 256*U columns and visits every row of it.  The peer table
+//   * A wavefront owns a tile of 64*U slices (256*U fp32 columns) and visits every row of it.  The peer table
 //     of a segment is a permutation, so the rows split into cycles i -> peers[i] -> ...
 //     Walking a cycle, the lane keeps the current and the next row's slice in registers,
 //     writes (cur + next) * 0.5f to the current row and moves on; the cycle's first slice
@@ -34,9 +35,11 @@
 //
 //  Both: tiles wholly inside one segment take the 16-byte vector path; the at most S+1
 //  tiles that straddle a segment boundary or the ragged row end run once per overlapped
-//  segment with per-element predication.  Row operators (MeanOp / FusedOp / PushOp) say
-//  what loading and storing a "gossiping row" means: the pairwise-tree mean of a group of
-//  G rows, the momentum-SGD update applied on the way in, or the push-sum de-biasing.
+//  segment with per-element predication.  Row operators (MeanOp / FusedOp / HierFusedOp /
+//  PushOp / Bf16Op) say what loading and storing a "gossiping row" means: the pairwise-tree
+//  mean of a group of G rows, the momentum-SGD update applied on the way in (to the row or
+//  to a group leader fed with the group's mean gradient), the push-sum de-biasing, or the
+//  bfloat16 unpacking and rounding.
 #ifndef CX_KERNELS_HPP
 #define CX_KERNELS_HPP
 #include "cx_mix.h"
@@ -592,10 +595,11 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
 
 // ---------------------------------------------------------------------------------
 // Row order of the out-of-place path.  Library-owned device memory (no allocation at run
-// time): kOrderSlots tables of kOrderEntries ints per GPU.  A slot belongs to ONE stream
-// and one entry point (first come, first served, for the life of the process): calls on a stream run in stream
-// order, so a slot is never rewritten while an earlier call still reads it.  Streams beyond
-// the first kOrderSlots run without a table (natural row order: same results, slower).
+// time): kOrderSlots tables of kOrderEntries ints per GPU and entry point.  A slot belongs
+// to ONE stream (first come, first served, for the life of the process): calls on a stream
+// run in stream order, so a slot is never rewritten while an earlier call still reads it.
+// Streams beyond the first kOrderSlots run without a table (natural row order: same
+// results, slower).
 // ---------------------------------------------------------------------------------
 constexpr int kOrderSlots = 4;
 constexpr int kOrderEntries = 1 << 18;
