@@ -39,7 +39,7 @@ def describe(wl) -> str:
 class Runner:
     """Holds one workload's device state and issues its steps."""
 
-    def __init__(self, wl, kind, total_rounds, in_place=False, bf16=False):
+    def __init__(self, wl, kind, total_rounds, in_place=False, rows16=None):
         import torch
         from paper_2012_15198_amd import cxmix as cx
         from paper_2012_15198_amd import workloads as WL
@@ -53,9 +53,9 @@ class Runner:
         self.in_place = in_place
         self.ld = (wl.P + 1023) // 1024 * 1024
         self.x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=self.ld, device=dev)
-        self.bf16 = bf16
-        if bf16:
-            self.x = self.x.to(torch.bfloat16)
+        self.rows16 = rows16                              # None (fp32 rows), "bf16" or "f16"
+        if rows16:
+            self.x = self.x.to(torch.bfloat16 if rows16 == "bf16" else torch.float16)
         self.y = self.x if in_place else torch.empty_like(self.x)
         self.n = wl.L if kind in ("hier", "hiersgd") else wl.W
         self.S = 1 if kind == "pushsum" else wl.S
@@ -64,7 +64,7 @@ class Runner:
         self.tab_host = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, pin_memory=True)
         self.tab_np = self.tab_host.numpy()
         self.tab_dev = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, device=dev)
-        self.bytes_per_elem = 4 if bf16 else 8
+        self.bytes_per_elem = 4 if rows16 else 8
         if kind == "fused":
             self.v = torch.zeros_like(self.x)
             self.v2 = self.v if in_place else torch.empty_like(self.v)
@@ -91,8 +91,9 @@ class Runner:
         if timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-        if self.kind == "gossip" and self.bf16:
-            cx.cx_gossip_mix_bf16(self.x, self.y, wl.P, self.so, tab)
+        if self.kind == "gossip" and self.rows16:
+            mix16 = cx.cx_gossip_mix_bf16 if self.rows16 == "bf16" else cx.cx_gossip_mix_f16
+            mix16(self.x, self.y, wl.P, self.so, tab)
         elif self.kind == "gossip":
             cx.cx_gossip_mix(self.x, self.y, wl.P, self.so, tab)
         elif self.kind == "hier":
@@ -141,10 +142,10 @@ class Runner:
         }
 
 
-def measured_traffic(workload, kind, in_place, bf16=False):
+def measured_traffic(workload, kind, in_place, rows16=None):
     """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
     WRITE_SIZE, scaled by the copy-kernel calibration), or None if there is none for this case."""
-    name = f"{workload}_{kind}{'_bf16' if bf16 else ''}_{'inplace' if in_place else 'pingpong'}_pmc.txt"
+    name = f"{workload}_{kind}{'_' + rows16 if rows16 else ''}_{'inplace' if in_place else 'pingpong'}_pmc.txt"
     path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
@@ -210,6 +211,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy", action="store_true")
     ap.add_argument("--bf16", action="store_true", help="bfloat16 rows (gossip only): cx_gossip_mix_bf16")
+    ap.add_argument("--f16", action="store_true", help="binary16 rows (gossip only): cx_gossip_mix_f16")
     ap.add_argument("--in-place", action="store_true",
                     help="update the matrix in place (cycle-walk kernel) instead of ping-pong buffers")
     args = ap.parse_args()
@@ -225,19 +227,22 @@ def main():
 
     wl = WL.WORKLOADS[args.workload]
     kind = args.kind or {"gossip": "gossip", "hier": "hier", "fused+pushsum": "fused"}[wl.kind]
-    if args.bf16 and kind != "gossip":
-        sys.exit("bench.py: --bf16 is available for the gossip entry point only")
-    runner = Runner(wl, kind, args.steps + args.warmup, in_place=args.in_place, bf16=args.bf16)
+    if args.bf16 and args.f16:
+        sys.exit("bench.py: --bf16 and --f16 exclude each other")
+    rows16 = "bf16" if args.bf16 else "f16" if args.f16 else None
+    if rows16 and kind != "gossip":
+        sys.exit("bench.py: --bf16 / --f16 are available for the gossip entry point only")
+    runner = Runner(wl, kind, args.steps + args.warmup, in_place=args.in_place, rows16=rows16)
     res = runner.run(args.steps, args.warmup)
     out = {
         "metric": "gossip-mix HBM GB/s and params-mixed/s per round (fraction of HBM peak), 1 GPU",
         "value": res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 rows, f32 arithmetic" if args.bf16 else "f32",
+        "scaling": "weak", "vs_baseline": None, "dtype": f"{rows16} rows, f32 arithmetic" if rows16 else "f32",
         "data": "synthetic",
         "config": {"workload": describe(wl) if kind != "gossip" or wl.G == 1 else describe(wl) + " (flat gossip over all rows)",
                    "entry_point": {"fused": "cx_sgd_fused_mix", "hiersgd": "cx_hier_sgd_fused_mix"}.get(
-                       kind, f"cx_{kind}_mix" + ("_bf16" if args.bf16 else "")),
+                       kind, f"cx_{kind}_mix" + ("_" + rows16 if rows16 else "")),
                    "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
                    "buffers": "in place" if args.in_place else "ping-pong (x_in -> x_out, swapped every round)",
                    "step": "cx_topology_gen(1 round) + table upload + one mixing launch"},
@@ -245,7 +250,7 @@ def main():
         "frac_of_hbm_peak": res["GBps"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": res["kernel_GBps"], "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": res["kernel_GBps"] / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(wl.name, kind, args.in_place, args.bf16),
+                     "traffic": measured_traffic(wl.name, kind, args.in_place, rows16),
                      "kernel": "mix_kernel" if args.in_place else "gather_kernel",
                      "kernel_ms_avg": res["kernel_ms_avg"],
                      "kernel_ms_min": res["kernel_ms_min"], "kernel_ms_median": res["kernel_ms_median"],
@@ -253,7 +258,7 @@ def main():
     }
     if not args.no_copy:
         out["copy_ceiling"] = copy_ceiling(res["alg_bytes_per_launch"])
-    if not args.no_cpu_baseline and kind == "gossip" and not args.bf16:
+    if not args.no_cpu_baseline and kind == "gossip" and not rows16:
         out["cpu_baseline"] = cpu_baseline(runner)
     else:
         out["cpu_baseline"] = None

@@ -212,6 +212,18 @@ int cx_gossip_mix_bf16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_
                        uint32_t flags, void *stream);
 
 /* ------------------------------------------------------------------------------------
+ * cx_gossip_mix_f16 -- the same on IEEE binary16 rows (the other 16-bit format of mixed
+ * precision training, Section 4.1): x is uint16 [W][ld] holding binary16 bit patterns,
+ * ld % 8 == 0,
+ *     x_out[i][c] = f16_rne((float(x_in[i][c]) + float(x_in[peers[s][i]][c])) * 0.5f),
+ * fp32 arithmetic, one rounding to binary16 (nearest even, gradual underflow, overflow to
+ * infinity; NaN stays a quiet NaN).  Everything else as cx_gossip_mix_bf16.
+ */
+int cx_gossip_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int64_t P,
+                      int32_t S, const int64_t *seg_off_dev, const int32_t *peers_dev,
+                      uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method).
  * cx_copy_baseline: dst[i] = src[i] for n floats (n % 4 == 0, 16-byte aligned) with the
  * same load/store instructions as the mixing kernels; the practical HBM ceiling and the

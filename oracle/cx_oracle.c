@@ -27,6 +27,7 @@
  * with one group equals SGD on the averaged gradient.  No function here is
  * "parity unpinned".
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -209,6 +210,62 @@ int oracle_gossip_mix_bf16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, in
                 float a = oracle_bf16_to_f32(x_in[i * ld + c]);
                 float b = oracle_bf16_to_f32(x_in[j * ld + c]);
                 x_out[i * ld + c] = oracle_f32_to_bf16((a + b) * 0.5f);
+            }
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* The same averaging on IEEE binary16 rows (1 sign, 5 exponent, 10 fraction  */
+/* bits, bias 15): widen, add and halve in fp32, round once to binary16       */
+/* (nearest, ties to even; gradual underflow; overflow to infinity).          */
+/* ------------------------------------------------------------------------- */
+float oracle_f16_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t e = (h >> 10) & 31u, m = h & 1023u;
+    float f;
+    if (e == 0) {                                   /* zero or subnormal: m * 2^-24 */
+        f = ldexpf((float)m, -24);
+        return sign ? -f : f;
+    }
+    uint32_t u = (e == 31) ? (sign | 0x7f800000u | (m << 13))      /* infinity, NaN */
+                           : (sign | ((e + 112u) << 23) | (m << 13));
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+uint16_t oracle_f32_to_f16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u) return (uint16_t)(sign | 0x7e00u | ((a >> 13) & 0x3ffu));   /* NaN stays NaN */
+    if (a >= 0x47800000u) return (uint16_t)(sign | 0x7c00u);       /* 2^16 and above, infinity */
+    if (a < 0x38800000u) {                          /* below 2^-14: a multiple of 2^-24 */
+        float mag;
+        memcpy(&mag, &a, sizeof mag);
+        uint32_t q = (uint32_t)nearbyintf(ldexpf(mag, 24));        /* 0..1024, ties to even */
+        return (uint16_t)(sign | q);
+    }
+    uint32_t kept_lsb = (a >> 13) & 1u;
+    a += 0xfffu + kept_lsb;                         /* round the 13 dropped bits, ties to even */
+    uint32_t h = (a >> 13) - (112u << 10);          /* may carry up to 0x7c00 = infinity */
+    return (uint16_t)(sign | h);
+}
+
+int oracle_gossip_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int64_t P,
+                          int32_t S, const int64_t *seg_off, const int32_t *peers)
+{
+    (void)P;
+    for (int32_t s = 0; s < S; ++s)
+        for (int32_t i = 0; i < W; ++i) {
+            int32_t j = peers[(int64_t)s * W + i];
+            for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+                float a = oracle_f16_to_f32(x_in[i * ld + c]);
+                float b = oracle_f16_to_f32(x_in[j * ld + c]);
+                x_out[i * ld + c] = oracle_f32_to_f16((a + b) * 0.5f);
             }
         }
     return 0;

@@ -23,7 +23,7 @@ __all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topo
            "gossip_mix", "hier_mix_f64", "hier_mix_f32", "sgd_fused_mix_f64",
            "sgd_fused_mix_f32", "pushsum_mix_f64", "pushsum_mix_f32",
            "hier_sgd_fused_mix_f64", "hier_sgd_fused_mix_f32", "gossip_mix_bf16", "f32_to_bf16",
-           "bf16_to_f32"]
+           "bf16_to_f32", "gossip_mix_f16", "f32_to_f16", "f16_to_f32"]
 
 
 def build_oracle(force: bool = False) -> str:
@@ -31,7 +31,7 @@ def build_oracle(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
                                "-fexcess-precision=standard", "-Wall", "-Wextra", "-shared",
-                               "-fPIC", "-o", _LIB, _SRC])
+                               "-fPIC", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 
@@ -57,6 +57,11 @@ def _L():
         lib.oracle_f32_to_bf16.argtypes = [f32]
         lib.oracle_bf16_to_f32.restype = f32
         lib.oracle_bf16_to_f32.argtypes = [ctypes.c_uint16]
+        lib.oracle_gossip_mix_f16.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp]
+        lib.oracle_f32_to_f16.restype = ctypes.c_uint16
+        lib.oracle_f32_to_f16.argtypes = [f32]
+        lib.oracle_f16_to_f32.restype = f32
+        lib.oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
         lib.oracle_hier_mix_f64.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_hier_mix_f32.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_sgd_fused_mix_f64.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32,
@@ -255,13 +260,35 @@ def bf16_to_f32(h) -> np.ndarray:
     return (h.astype(np.uint32) << 16).view(np.float32)
 
 
-def gossip_mix_bf16(x, P, seg_off, peers) -> np.ndarray:
-    """x: uint16 [W][ld] of bfloat16 bit patterns; returns the mixed patterns."""
+def _mix16(fn, name, x, P, seg_off, peers):
     x = _mat(x, dtype=np.uint16)
     W, ld = x.shape
     so = _seg(seg_off, P)
     S = len(so) - 1
     pe = _peers(peers, S, W)
     out = x.copy()
-    _check(_L().oracle_gossip_mix_bf16(_p(x), _p(out), ld, W, P, S, _p(so), _p(pe)), "gossip_mix_bf16")
+    _check(fn(_p(x), _p(out), ld, W, P, S, _p(so), _p(pe)), name)
     return out
+
+
+def gossip_mix_bf16(x, P, seg_off, peers) -> np.ndarray:
+    """x: uint16 [W][ld] of bfloat16 bit patterns; returns the mixed patterns."""
+    return _mix16(_L().oracle_gossip_mix_bf16, "gossip_mix_bf16", x, P, seg_off, peers)
+
+
+def f32_to_f16(a) -> np.ndarray:
+    """IEEE binary16 bit patterns (uint16) of float32 values, round-to-nearest-even."""
+    a = np.asarray(a, dtype=np.float32)
+    fn = _L().oracle_f32_to_f16
+    return np.array([fn(float(v)) for v in a.ravel()], dtype=np.uint16).reshape(a.shape)
+
+
+def f16_to_f32(h) -> np.ndarray:
+    h = np.asarray(h, dtype=np.uint16)
+    fn = _L().oracle_f16_to_f32
+    return np.array([fn(int(v)) for v in h.ravel()], dtype=np.float32).reshape(h.shape)
+
+
+def gossip_mix_f16(x, P, seg_off, peers) -> np.ndarray:
+    """x: uint16 [W][ld] of binary16 bit patterns; returns the mixed patterns."""
+    return _mix16(_L().oracle_gossip_mix_f16, "gossip_mix_f16", x, P, seg_off, peers)

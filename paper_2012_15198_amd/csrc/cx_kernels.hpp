@@ -36,7 +36,7 @@
 //  Both: tiles wholly inside one segment take the 16-byte vector path; the at most S+1
 //  tiles that straddle a segment boundary or the ragged row end run once per overlapped
 //  segment with per-element predication.  Row operators (MeanOp / FusedOp / HierFusedOp /
-//  PushOp / Bf16Op) say what loading and storing a "gossiping row" means: the pairwise-tree
+//  PushOp / Row16Op) say what loading and storing a "gossiping row" means: the pairwise-tree
 //  mean of a group of G rows, the momentum-SGD update applied on the way in (to the row or
 //  to a group leader fed with the group's mean gradient), the push-sum de-biasing, or the
 //  bfloat16 unpacking and rounding.
@@ -280,10 +280,14 @@ struct HierFusedOp {
 };
 
 // ---------------------------------------------------------------------------------
-// bfloat16 rows (8 columns per 16-byte slice), averaged in fp32:
-//     out = bf16_rne((float(a) + float(b)) * 0.5f)
+// 16-bit rows (8 columns per 16-byte slice), bfloat16 or IEEE binary16, averaged in fp32:
+//     out = round_to_nearest_even_16((float(a) + float(b)) * 0.5f)
 // ---------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_float(unsigned h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ float f16_bits_to_float(unsigned h)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));   // exact, subnormals kept
+}
 
 template <int U, bool FULL, bool NT>
 __device__ __forceinline__ void tile_load16(const uint16_t *p, const unsigned (&mask)[U], Tile<U> &raw)
@@ -323,11 +327,12 @@ __device__ __forceinline__ void tile_store16(uint16_t *p, const unsigned (&mask)
     }
 }
 
-struct Bf16Op {
-    static constexpr int kElems = 8;                       // bf16 columns per 16-byte slice
+template <bool IEEE_HALF>
+struct Row16Op {
+    static constexpr int kElems = 8;                       // 16-bit columns per 16-byte slice
     template <int U> using Work = Tile<2 * U>;             // 8 fp32 values per slice
     static constexpr int kRawPerSlice = 1;
-    template <int U> struct Raw { Tile<U> x; };            // packed bf16 pairs, as loaded
+    template <int U> struct Raw { Tile<U> x; };            // packed 16-bit pairs, as loaded
     const uint16_t *xin;
     uint16_t *xout;
     int64_t ld;
@@ -345,8 +350,10 @@ struct Bf16Op {
         for (int u = 0; u < U; ++u) {
             const u4 w = __builtin_bit_cast(u4, raw.x.v[u]);
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                t.v[2 * u + (e >> 2)][e & 3] = bf16_bits_to_float((w[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+            for (int e = 0; e < 8; ++e) {
+                const unsigned h = (w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
+                t.v[2 * u + (e >> 2)][e & 3] = IEEE_HALF ? f16_bits_to_float(h) : bf16_bits_to_float(h);
+            }
         }
     }
     template <int U, bool FULL, bool NT>
@@ -355,21 +362,26 @@ struct Bf16Op {
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
         typedef float f2 __attribute__((ext_vector_type(2)));
         typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
         Tile<U> packed;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             u4 w;
 #pragma unroll
             for (int pair = 0; pair < 4; ++pair) {
-                // two fp32 -> one packed bf16 pair, round-to-nearest-even in hardware
+                // two fp32 -> one packed 16-bit pair, round-to-nearest-even in hardware
                 const f2 two = {t.v[2 * u + (pair >> 1)][2 * (pair & 1)], t.v[2 * u + (pair >> 1)][2 * (pair & 1) + 1]};
-                w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
+                if constexpr (IEEE_HALF) w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, h2));
+                else w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
             }
             packed.v[u] = __builtin_bit_cast(f4, w);
         }
         tile_store16<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
     }
 };
+
+using Bf16Op = Row16Op<false>;
+using Fp16Op = Row16Op<true>;
 
 // Push-sum: plain rows, optional de-biased copy z = x' / w'.
 struct PushOp {

@@ -95,12 +95,15 @@ def test_c2_whole_matrix_three_rounds_and_sampled_all_rounds():
     free(a, b, c, xd)
 
 
-def test_c2_bf16_rows_sampled_all_rounds():
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_c2_16bit_rows_sampled_all_rounds(fmt):
     wl = WL.WORKLOADS["C2"]
     so = WL.equal_seg_off(wl.P, wl.S)
     ld = padded(wl.P)
     tabs = cx.cx_topology_gen(wl.seed, wl.W, wl.S, 0, wl.rounds)
-    xd = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld).to(torch.bfloat16)
+    mix, omix, dt = {"bf16": (cx.cx_gossip_mix_bf16, O.gossip_mix_bf16, torch.bfloat16),
+                     "f16": (cx.cx_gossip_mix_f16, O.gossip_mix_f16, torch.float16)}[fmt]
+    xd = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld).to(dt)
     cols, sso, cold = sample(wl, so)
     grab = lambda t: host(t.view(torch.int16).index_select(1, cold)).view(np.uint16)
     sub = grab(xd)
@@ -108,10 +111,10 @@ def test_c2_bf16_rows_sampled_all_rounds():
     sod = dev(so)
     for r in range(wl.rounds):
         t = dev(tabs[r])
-        cx.cx_gossip_mix_bf16(a, b, wl.P, sod, t)
+        mix(a, b, wl.P, sod, t)
         a, b = b, a
-        cx.cx_gossip_mix_bf16(c, c, wl.P, sod, t)
-        sub = O.gossip_mix_bf16(sub, len(cols), sso, tabs[r])
+        mix(c, c, wl.P, sod, t)
+        sub = omix(sub, len(cols), sso, tabs[r])
     torch.cuda.synchronize()
     assert (grab(a) == sub).all() and (grab(c) == sub).all()
     free(a, b, c, xd)

@@ -273,6 +273,74 @@ def test_gossip_bf16_rounds_edge_values_every_launch_shape(tuning):
     assert same_bf16(host(a).view(np.uint16), want) and same_bf16(host(y0).view(np.uint16), want)
 
 
+# ------------------------------------------------------------------- IEEE binary16 rows
+def same_f16(a, b):
+    isnan = lambda h: ((h & 0x7C00) == 0x7C00) & ((h & 0x03FF) != 0)
+    return bool(((a == b) | (isnan(a) & isnan(b))).all())
+
+
+@pytest.mark.parametrize("W,P,ld,S", [(2, 1, 8, 1), (2, 13, 16, 2), (3, 2048, 2048, 1), (8, 9001, 9008, 4),
+                                      (5, 8195, 8320, 7), (33, 5003, 5008, 8), (64, 3000, 3000, 5)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_gossip_f16_bit_exact(W, P, ld, S, inplace):
+    xh = O.f32_to_f16(WL.gen_matrix(W, P, 1.0, seed=W * 7 + P, ld=ld))
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(73, W, S, 0, 1)[0]
+    want = O.gossip_mix_f16(xh, P, so, pe)
+    xd = dev(xh.view(np.int16))
+    out = xd if inplace else xd.clone()
+    cx.cx_gossip_mix_f16(xd, out, P, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    assert same_f16(host(out).view(np.uint16), want)
+
+
+@pytest.mark.parametrize("tuning", ALL_TUNINGS)
+def test_gossip_f16_every_bit_pattern_every_launch_shape(tuning):
+    # half of the entries are uniform over all 65536 patterns (subnormals, the overflow range,
+    # infinities, NaNs), the rest N(0,1); pairs that overflow or underflow when averaged occur
+    W, P, ld, S, R = 10, 12345, 12352, 6, 3
+    rng = np.random.default_rng(74)
+    xh = O.f32_to_f16(WL.gen_matrix(W, ld, 1.0, seed=74))
+    raw = rng.integers(0, 65536, size=xh.shape).astype(np.uint16)
+    xh = np.where(rng.random(xh.shape) < 0.5, raw, xh)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(74, W, S, 0, R)
+    want = xh
+    for r in range(R):
+        want = O.gossip_mix_f16(want, P, so, tabs[r])
+    with Tuning(*tuning):
+        a = dev(xh.view(np.int16))
+        y0, y1 = dev(xh.view(np.int16)), dev(xh.view(np.int16))
+        for r in range(R):
+            cx.cx_gossip_mix_f16(a, a, P, dev(so), dev(tabs[r]))
+            cx.cx_gossip_mix_f16(y0, y1, P, dev(so), dev(tabs[r]))
+            y0, y1 = y1, y0
+        torch.cuda.synchronize()
+    assert same_f16(host(a).view(np.uint16), want) and same_f16(host(y0).view(np.uint16), want)
+
+
+def test_gossip_f16_all_pairs_of_a_pattern_sample():
+    # every pair from 181 chosen patterns (all exponents, both signs, mantissa extremes) as
+    # (row 0, row 1): the rounding of each average is checked against the oracle
+    pats = sorted({(s << 15) | (e << 10) | m for s in (0, 1) for e in range(32)
+                   for m in (0, 1, 0x3FF)} | {0x3555, 0x1234, 0x7BFE, 0x0002, 0x83FE})
+    pats = np.array([p for p in pats if not ((p & 0x7C00) == 0x7C00 and (p & 0x3FF))], dtype=np.uint16)
+    n = len(pats)
+    P = n * n
+    ld = (P + 7) // 8 * 8
+    x = np.zeros((2, ld), dtype=np.uint16)
+    x[0, :P] = np.repeat(pats, n)
+    x[1, :P] = np.tile(pats, n)
+    so = WL.equal_seg_off(P, 1)
+    pe = np.array([[1, 0]], dtype=np.int32)
+    want = O.gossip_mix_f16(x, P, so, pe)
+    xd = dev(x.view(np.int16))
+    out = torch.empty_like(xd)
+    cx.cx_gossip_mix_f16(xd, out, P, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    assert same_f16(host(out).view(np.uint16)[:, :P], want[:, :P])
+
+
 # ------------------------------------------------------------------------ hierarchical
 def hier_tol(x, G, P, y64, pe, so):
     """1e-6 relative to max(|ref|, mean |x| over the rows that enter the result)."""

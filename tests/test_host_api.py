@@ -142,14 +142,15 @@ def test_mix_calls_reject_bad_arguments_on_the_host():
     assert hfused(v_in=A, v_out=A) == -6 and hfused(g=A) == -6 and hfused(g=C) == -6
     assert hfused(G=16, W=32) == -8 and hfused(g=D + 4) == -5
 
-    def bf16(**kw):
+    def bf16(fn=None, **kw):
         a = {**ok, **kw}
-        return L.cx_gossip_mix_bf16(a["x_in"], a["x_out"], a["ld"], a["W"], a["P"], a["S"], a["so"],
-                                    a["pe"], a["flags"], a["st"])
+        return (fn or L.cx_gossip_mix_bf16)(a["x_in"], a["x_out"], a["ld"], a["W"], a["P"], a["S"], a["so"],
+                                            a["pe"], a["flags"], a["st"])
 
-    assert bf16(x_in=None) == -1 and bf16(W=1) == -2 and bf16(ld=56) == -2
-    assert bf16(ld=60, P=60) == -5                          # bf16 rows need ld % 8 == 0
-    assert bf16(x_out=A + 32) == -6 and bf16(flags=4) == -8
+    for fn in (L.cx_gossip_mix_bf16, L.cx_gossip_mix_f16):
+        assert bf16(fn, x_in=None) == -1 and bf16(fn, W=1) == -2 and bf16(fn, ld=56) == -2
+        assert bf16(fn, ld=60, P=60) == -5                  # 16-bit rows need ld % 8 == 0
+        assert bf16(fn, x_out=A + 32) == -6 and bf16(fn, flags=4) == -8
 
     assert L.cx_copy_baseline(None, B, 64, None) == -1
     assert L.cx_copy_baseline(A, B, 6, None) == -2

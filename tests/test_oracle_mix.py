@@ -412,3 +412,67 @@ def test_bf16_mix_hand_case_and_agreement_with_the_fp32_mix():
     # identical rows stay fixed; the column mean moves by at most half a bf16 ulp per round
     same = np.tile(xb[:1], (W, 1))
     assert (O.gossip_mix_bf16(same, P, so, pe) == same).all()
+
+
+def test_f16_widening_matches_the_library_on_every_bit_pattern():
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    got = O.f16_to_f32(h)
+    ref = h.view(np.float16).astype(np.float32)
+    nan = np.isnan(ref)
+    assert (np.isnan(got) == nan).all()
+    assert (got.view(np.uint32)[~nan] == ref.view(np.uint32)[~nan]).all()
+    # hand values: smallest subnormal, largest subnormal, smallest normal, largest finite
+    assert O.f16_to_f32([0x0001, 0x03FF, 0x0400, 0x7BFF, 0xC000]).tolist() == \
+        [2.0 ** -24, 1023 * 2.0 ** -24, 2.0 ** -14, 65504.0, -2.0]
+
+
+def test_f16_rounding_by_hand_and_against_the_library_conversion():
+    # 1 + 2^-11 is a tie between 1.0 and 1 + 2^-10: even mantissa wins; a hair above goes up
+    assert O.f32_to_f16([1.0, 1.0 + 2 ** -11, 1.0 + 2 ** -11 + 2 ** -20, 1.0 + 3 * 2 ** -11]).tolist() == \
+        [0x3C00, 0x3C00, 0x3C01, 0x3C02]
+    # overflow: 65519.99 stays finite, the tie 65520 and everything above become infinity
+    assert O.f32_to_f16([65504.0, 65519.996, 65520.0, 1e9, -65520.0, np.inf]).tolist() == \
+        [0x7BFF, 0x7BFF, 0x7C00, 0x7C00, 0xFC00, 0x7C00]
+    # gradual underflow: multiples of 2^-24, ties to even, below half of the smallest -> signed zero
+    assert O.f32_to_f16([2.0 ** -24, 1.5 * 2.0 ** -24, 2.5 * 2.0 ** -24, 2.0 ** -25, -2.0 ** -25,
+                         1.0001 * 2.0 ** -25, 1023.5 * 2.0 ** -24, 2.0 ** -14]).tolist() == \
+        [0x0001, 0x0002, 0x0002, 0x0000, 0x8000, 0x0001, 0x0400, 0x0400]
+    assert (O.f32_to_f16([np.nan]) & 0x7E00 == 0x7E00).all()
+    rng = np.random.default_rng(16)
+    vals = np.concatenate([
+        rng.standard_normal(4000).astype(np.float32),
+        (rng.standard_normal(2000) * 1e-6).astype(np.float32),          # subnormal range
+        (rng.standard_normal(2000) * 3e4).astype(np.float32),           # around the overflow point
+        rng.integers(0, 2 ** 32, 4000, dtype=np.uint64).astype(np.uint32).view(np.float32)])
+    vals = vals[~np.isnan(vals)]
+    with np.errstate(over="ignore"):
+        ref = vals.astype(np.float16).view(np.uint16)
+    assert (O.f32_to_f16(vals) == ref).all()
+    # widening then narrowing is the identity on every non-NaN pattern
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    keep = ~np.isnan(h.view(np.float16))
+    assert (O.f32_to_f16(O.f16_to_f32(h[keep])) == h[keep]).all()
+
+
+def test_f16_mix_hand_case_and_agreement_with_the_fp32_mix():
+    # 1.0 and 1 + 2^-10 (adjacent): the mean is a tie and goes to the even mantissa (1.0);
+    # 60000 and 65504 average to 62752 exactly; 2^-24 and 0 average to 2^-25, a tie -> zero
+    x = O.f32_to_f16([[1.0, 60000.0, 2.0 ** -24], [1.0 + 2 ** -10, 65504.0, 0.0]])
+    y = O.gossip_mix_f16(x, 3, [0, 3], [[1, 0]])
+    assert O.f16_to_f32(y).tolist() == [[1.0, 62752.0, 0.0]] * 2
+    W, P, S = 6, 300, 3
+    xh = O.f32_to_f16(WL.gen_matrix(W, P, 1.0, 31))
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(31, W, S, 0, 1)[0]
+    yh = O.gossip_mix_f16(xh, P, so, pe)
+    # equals the fp32 oracle on the widened inputs followed by one rounding
+    want = O.f32_to_f16(O.gossip_mix(O.f16_to_f32(xh), P, so, pe))
+    assert (yh == want).all()
+    # and the library's float16 does the same from the exact (float64) average
+    for s in range(S):
+        lo, hi = so[s], so[s + 1]
+        ex = (xh.view(np.float16).astype(np.float64)[:, lo:hi] +
+              xh.view(np.float16).astype(np.float64)[pe[s], lo:hi]) / 2
+        assert (ex.astype(np.float16).view(np.uint16) == yh[:, lo:hi]).all()
+    same = np.tile(xh[:1], (W, 1))
+    assert (O.gossip_mix_f16(same, P, so, pe) == same).all()
