@@ -175,6 +175,29 @@ def copy_ceiling(nbytes, reps=10):
     return {"GBps": 8.0 * n / (ms * 1e-3) / 1e9, "ms": ms, "bytes": 8 * n}
 
 
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def topology_gen_time(runner):
+    """Host time of cx_topology_gen for the workload's whole table (all its rounds), outside the timed region."""
+    wl, cx = runner.wl, runner.cx
+    buf = np.empty((wl.rounds, runner.S, runner.n), dtype=np.int32)
+    best = float("inf")
+    for _ in range(5):
+        t0 = time.perf_counter()
+        cx.cx_topology_gen(wl.seed, runner.n, runner.S, 0, wl.rounds, runner.mode, out=buf)
+        best = min(best, time.perf_counter() - t0)
+    return {"host_ms_whole_table": best * 1e3, "rounds": wl.rounds, "segments": runner.S, "ranks": runner.n,
+            "host_us_per_round": best * 1e6 / wl.rounds}
+
+
 def cpu_baseline(runner, budget_s=12.0):
     """The CPU oracle, as it stands, timed on this host: full rounds of the same workload."""
     import oracle as O
@@ -196,7 +219,7 @@ def cpu_baseline(runner, budget_s=12.0):
             "params_mixed_per_s": elems * rounds / dt, "s_per_round": dt / rounds,
             "cores": 1, "kind": "oracle",
             "sample": f"{rounds} full rounds of {describe(wl)} (oracle_gossip_mix, single thread, "
-                      f"{os.cpu_count()} host cores visible)"}
+                      f"{os.cpu_count()} host cores visible, {cpu_model()})"}
 
 
 def main():
@@ -256,6 +279,9 @@ def main():
                      "kernel_ms_min": res["kernel_ms_min"], "kernel_ms_median": res["kernel_ms_median"],
                      "alg_bytes_per_launch": res["alg_bytes_per_launch"]},
     }
+    traffic = out["roofline"]["traffic"]
+    out["roofline"]["measured_GBps"] = traffic / (res["kernel_ms_avg"] * 1e-3) / 1e9 if traffic else None
+    out["topology_gen"] = topology_gen_time(runner)
     if not args.no_copy:
         out["copy_ceiling"] = copy_ceiling(res["alg_bytes_per_launch"])
     if not args.no_cpu_baseline and kind == "gossip" and not rows16:

@@ -92,12 +92,28 @@ def test_gossip_ragged_and_degenerate_segments():
     assert same_bits(run_gossip(x2, P2, so2, pe2, False), O.gossip_mix(x2, P2, so2, pe2))
 
 
-def test_gossip_max_rows():
+@pytest.mark.parametrize("inplace", [True, False])
+def test_gossip_max_rows(inplace):
     W, P = cx.CX_MAX_ROWS, 520
     x = WL.gen_matrix(W, P, 1.0, seed=23)
     so = WL.equal_seg_off(P, 2)
     pe = O.topology(23, W, 2, 0, 1)[0]
-    assert same_bits(run_gossip(x, P, so, pe, True), O.gossip_mix(x, P, so, pe))
+    assert same_bits(run_gossip(x, P, so, pe, inplace), O.gossip_mix(x, P, so, pe))
+
+
+def test_hier_max_rows_and_many_leaders():
+    # 1024 rows in groups of 2: 512 leaders, the longest leader table the library takes
+    W, P, G, S = cx.CX_MAX_ROWS, 300, 2, 3
+    x = WL.gen_matrix(W, P, 1.0, seed=25)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(25, W // G, S, 0, 1)[0]
+    want = O.hier_mix_f32(x, P, G, so, pe)
+    for inplace in (True, False):
+        xd = dev(x)
+        out = xd if inplace else torch.full_like(xd, float("nan"))
+        cx.cx_hier_mix(xd, out, P, G, dev(so), dev(pe))
+        torch.cuda.synchronize()
+        assert same_bits(host(out)[:, :P], want[:, :P])
 
 
 def test_tables_that_are_not_permutations():
