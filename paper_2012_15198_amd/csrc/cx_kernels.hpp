@@ -18,9 +18,13 @@
 //     neighbouring chunks row after row; rows follow the cycles of the peer permutation,
 //     so a block's partner is the next block's own row).
 //   * Long contiguous row visits per XCD keep the DRAM row buffers busy, which a kernel
-//     whose waves each wander over all rows cannot do (measured: 74 % vs 66 % of peak).
+//     whose waves each wander over all rows cannot do (measured: 75 % vs 67 % of peak).
 //   * order_kernel, a few microseconds ahead of it, derives the row order from the
-//     device-resident peer table into library-owned device memory (no allocation).
+//     device-resident peer table into library-owned device memory (no allocation): one word
+//     per (cluster, position) with the row, its partner and a "one segment covers this
+//     cluster" bit, so almost every workgroup starts its loads after one scalar load.
+//     Workgroups are many and small (one slice per lane for plain gossip): their count of
+//     instructions, not only their bytes, decides the rate.
 //
 //  mix_kernel (in place capable) -- the column-owner cycle walk.
 //   * A wavefront owns a tile of 64*U slices (256*U fp32 columns) and visits every row of it.  The peer table
@@ -149,12 +153,20 @@ __device__ __forceinline__ Tile<U> tree_sum(const Tile<U> *r)
 // Each operator splits "load gossiping row r" into issue() -- put the row's global loads in
 // flight into a Raw slot -- and finish() -- turn the arrived data into the tile that takes
 // part in the pairwise average.  kRawPerSlice = 16-byte registers per slice and slot.
+// kGather = the operator's default launch shape in the out-of-place kernel.
+struct GatherShape {
+    int U, waves, visit_kb;
+};
+
 // Plain gossip (G == 1) and hierarchical mode (a gossiping row = a group of G rows).
 template <int G>
 struct MeanOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = G;
+    // out-of-place launch: slices per lane, waves per workgroup, KB of one visit to a gossiping row
+    // (all G rows behind it) per XCD -- measured optima on MI355X
+    static constexpr GatherShape kGather = G == 1 ? GatherShape{1, 4, 256} : GatherShape{1, 8, 1024};
     template <int U> struct Raw { Tile<U> r[G]; };
     const float *xin;
     float *xout;
@@ -193,6 +205,7 @@ struct FusedOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = 3;
+    static constexpr GatherShape kGather{1, 8, 256};   // out-of-place launch: slices, waves, row visit KB per XCD
     template <int U> struct Raw { Tile<U> x, v, g; };
     const float *xin;
     float *xout;
@@ -238,6 +251,7 @@ struct HierFusedOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = G + 2;
+    static constexpr GatherShape kGather{1, 8, 1024};  // out-of-place launch: slices, waves, group visit KB per XCD
     template <int U> struct Raw { Tile<U> g[G], x, v; };
     const float *xin;
     float *xout;
@@ -332,6 +346,7 @@ struct Row16Op {
     static constexpr int kElems = 8;                       // 16-bit columns per 16-byte slice
     template <int U> using Work = Tile<2 * U>;             // 8 fp32 values per slice
     static constexpr int kRawPerSlice = 1;
+    static constexpr GatherShape kGather{2, 8, 128};   // out-of-place launch: slices, waves, row visit KB per XCD
     template <int U> struct Raw { Tile<U> x; };            // packed 16-bit pairs, as loaded
     const uint16_t *xin;
     uint16_t *xout;
@@ -388,6 +403,7 @@ struct PushOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = 1;
+    static constexpr GatherShape kGather{2, 4, 512};   // out-of-place launch: slices, waves, row visit KB per XCD
     template <int U> struct Raw { Tile<U> x; };
     const float *xin;
     float *xout;
@@ -607,15 +623,35 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
 
 // ---------------------------------------------------------------------------------
 // Row order of the out-of-place path.  Library-owned device memory (no allocation at run
-// time): kOrderSlots tables of kOrderEntries ints per GPU and entry point.  A slot belongs
+// time): kOrderSlots tables of kOrderEntries words per GPU and entry point.  A slot belongs
 // to ONE stream (first come, first served, for the life of the process): calls on a stream
 // run in stream order, so a slot is never rewritten while an earlier call still reads it.
 // Streams beyond the first kOrderSlots run without a table (natural row order: same
 // results, slower).
+//
+// Entry (cluster, k): the k-th row the cluster's workgroups visit, that row's partner in the
+// segment of the cluster's first column, and a flag saying that this segment covers every
+// column of the cluster (so a whole tile of the cluster needs no segment lookup at all).
 // ---------------------------------------------------------------------------------
 constexpr int kOrderSlots = 4;
 constexpr int kOrderEntries = 1 << 18;
-__device__ int g_order[kOrderSlots][kOrderEntries];
+constexpr int kOrderRowBits = 10;                     // CX_MAX_ROWS == 1 << kOrderRowBits
+constexpr unsigned kOrderRowField = (1u << kOrderRowBits) - 1u;
+constexpr unsigned kOrderOneSegment = 1u << (2 * kOrderRowBits);
+static_assert(CX_MAX_ROWS <= (1 << kOrderRowBits), "row ids must fit the order table's fields");
+__device__ unsigned g_order[kOrderSlots][kOrderEntries];
+
+// The row that gossiping row `row` averages with in segment s (Algorithm 1: receive_from):
+// the fixed shift of the push-sum schedule, or the peer table's entry; an entry outside
+// [0, n) means the row itself.
+__device__ __forceinline__ int partner_of(const int32_t *__restrict__ peers, int shift, int n, int s, int row)
+{
+    int peer = row;
+    if (shift > 0) peer = row >= shift ? row - shift : row - shift + n;
+    else if (peers) peer = peers[static_cast<int64_t>(s) * n + row];
+    if (static_cast<unsigned>(peer) >= static_cast<unsigned>(n)) peer = row;
+    return peer;
+}
 
 // One workgroup per segment: builds the segment's cycle schedule and writes it as the row
 // order of every cluster whose first column lies in that segment.
@@ -637,11 +673,16 @@ __global__ __launch_bounds__(256) void order_kernel(int n, int64_t P, int S,
     const int64_t c_lo = (sb + cluster_cols - 1) / cluster_cols;
     int64_t c_hi = (se + cluster_cols - 1) / cluster_cols;
     if (c_hi > nclusters) c_hi = nclusters;
-    int *order = g_order[slot];
+    unsigned *order = g_order[slot];
     for (int64_t idx = threadIdx.x; idx < (c_hi - c_lo) * n; idx += blockDim.x) {
         const int64_t c = c_lo + idx / n;
         const int k = static_cast<int>(idx % n);
-        order[c * n + k] = sched[k] & kRowMask;
+        const int row = sched[k] & kRowMask;
+        const int64_t last_col = (c + 1) * cluster_cols < P ? (c + 1) * cluster_cols : P;
+        unsigned e = static_cast<unsigned>(row) |
+                     (static_cast<unsigned>(partner_of(peers, shift, n, s, row)) << kOrderRowBits);
+        if (last_col <= se) e |= kOrderOneSegment;
+        order[c * n + k] = e;
     }
 }
 
@@ -663,55 +704,95 @@ __global__ __launch_bounds__(256) void order_kernel(int n, int64_t P, int S,
 template <class Op, int U, bool NT>
 __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     Op op, int n, int64_t P, int S, const int64_t *__restrict__ seg_off,
-    const int32_t *__restrict__ peers, int shift, int skip_mix, int64_t nchunks, int CL,
-    int xcd_shift, int order_slot)
+    const int32_t *__restrict__ peers, int shift, int skip_mix, unsigned nchunks, unsigned CL,
+    unsigned nwaves, int xcd_shift, int order_slot)
 {
     // grid: x = (chunk within cluster, xcd) with the xcd in the low bits, y = gossiping row,
     // z = cluster.  Blocks are dispatched x-fastest, so an XCD sees, for one cluster, row 0's
     // CL chunks, then row 1's, ... and no integer division is needed to decode the block.
+    // Chunk and tile numbers fit 32 bits (checked by the host), so the block is decoded with
+    // a handful of scalar instructions, and the two ways out of the grid's padding share one
+    // branch: the kernel's arguments are fetched once, ahead of it.
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = uniform(threadIdx.x >> 6);
-    const int nwaves = blockDim.x >> 6;
-    const int xcd = blockIdx.x & ((1 << xcd_shift) - 1);
-    const int t = blockIdx.x >> xcd_shift;
-    const int64_t cluster = (static_cast<int64_t>(blockIdx.z) << xcd_shift) + xcd;
-    const int64_t chunk = cluster * CL + t;
-    if (chunk >= nchunks) return;
-    // y is the position in the cluster's row order: with the order kernel's table, rows follow
-    // the permutation cycles, so this block's partner is the next block's own row (fresh in L2)
-    int row = blockIdx.y;
-    if (order_slot >= 0) {
-        row = g_order[order_slot][cluster * n + blockIdx.y];
-        if (static_cast<unsigned>(row) >= static_cast<unsigned>(n)) row = blockIdx.y;
-    }
-
+    const unsigned wave = uniform(threadIdx.x >> 6);
+    const unsigned xcd = blockIdx.x & ((1u << xcd_shift) - 1u);
+    const unsigned t = blockIdx.x >> xcd_shift;
+    const unsigned cluster = (blockIdx.z << xcd_shift) + xcd;
+    const unsigned chunk = cluster * CL + t;
     constexpr int kSliceCols = Op::kElems;
     constexpr int kTileCols = kWave * kSliceCols * U;
-    const int64_t c0 = (chunk * nwaves + wave) * kTileCols;
-    if (c0 >= P) return;
+    const int64_t c0 = static_cast<int64_t>(chunk * nwaves + wave) * kTileCols;
+    if (chunk >= nchunks || c0 >= P) return;
     const int64_t c1 = (c0 + kTileCols < P) ? c0 + kTileCols : P;
     const int64_t off = c0 + kSliceCols * lane;
-    const bool whole = c0 + kTileCols <= P;      // the tile does not hang over the row end
-
-    // The row's own data does not depend on the segment: put its loads in flight first and
-    // look the segment and the partner up while they travel.
-    typename Op::template Raw<U> mine;
     unsigned full_mask[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) full_mask[u] = (1u << kSliceCols) - 1u;
-    if (whole) op.template issue<U, true, false>(row, off, full_mask, mine);
 
-    // Segment and partner lookup.  With up to 63 segments one vector load brings the whole
-    // offset table and this row's partner in every segment into lanes 0..S at once (a single
-    // memory latency); the segment of c0 is then a ballot + popcount and the table entries
-    // are read across lanes.  Longer tables fall back to a scalar binary search.
+    // `mine` holds (or will hold) this row's data; average it with the partner's and store.
+    // Operators with many rows behind a gossiping row (hierarchical groups) reduce their
+    // own rows before the partner's are requested, which halves the registers in flight.
+    int row = blockIdx.y;
+    typename Op::template Raw<U> mine;
+    auto mix_and_store = [&](auto full_c, const unsigned (&m)[U], int peer) {
+        constexpr bool FULL = decltype(full_c)::value;
+        constexpr bool kOneAtATime = Op::kRawPerSlice * U >= 16;
+        typename Op::template Work<U> a, out;
+        if (skip_mix) {
+            op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
+            out = a;
+        } else {
+            typename Op::template Work<U> c;
+            if constexpr (kOneAtATime) {
+                op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
+                op.template issue<U, FULL, false>(peer, off, m, mine);
+                op.template finish<U, FULL, NT, false>(peer, off, m, mine, c);
+            } else {
+                typename Op::template Raw<U> theirs;
+                op.template issue<U, FULL, false>(peer, off, m, theirs);
+                op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
+                op.template finish<U, FULL, NT, false>(peer, off, m, theirs, c);
+            }
+#pragma unroll
+            for (int u = 0; u < Op::template Work<U>::kN; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
+        }
+        op.template store<U, FULL, NT>(row, off, m, out);
+    };
+
+    // y is the position in the cluster's row order: with the order kernel's table, rows follow
+    // the permutation cycles, so this block's partner is the next block's own row (fresh in L2).
+    // Fast path, almost every tile: the table entry also names the partner and says that one
+    // segment covers the cluster, so a tile that does not hang over the row end starts all its
+    // loads after a single scalar load.  Whatever the table holds, no access leaves the
+    // matrix: rows are checked against n and the tile against P.
+    if (order_slot >= 0) {
+        const unsigned e = g_order[order_slot][cluster * static_cast<unsigned>(n) + blockIdx.y];
+        const int r = static_cast<int>(e & kOrderRowField);
+        const int q = static_cast<int>((e >> kOrderRowBits) & kOrderRowField);
+        if (r < n) row = r;
+        if ((e & kOrderOneSegment) != 0 && r < n && q < n && c0 + kTileCols <= P) {
+            op.template issue<U, true, false>(row, off, full_mask, mine);
+            mix_and_store(std::true_type{}, full_mask, q);
+            return;
+        }
+    }
+
+    // General path: tiles of clusters that a segment boundary or the row end crosses, and every
+    // tile when there is no order table.  With up to 63 segments one vector load brings the
+    // whole offset table and this row's partner in every segment into lanes 0..S at once (a
+    // single memory latency); the segment of c0 is then a ballot + popcount and the table
+    // entries are read across lanes.  Longer tables fall back to a scalar binary search.
+    // The row's own data does not depend on the segment: a tile that does not hang over the
+    // row end puts its loads in flight before the lookup.
+    const bool whole = c0 + kTileCols <= P;
+    if (whole) op.template issue<U, true, false>(row, off, full_mask, mine);
     const bool in_lanes = S <= 63;
     int64_t lane_off = 0;
     int lane_peer = row;
     int first_seg;
     if (in_lanes) {
         if (lane <= S && S > 1) lane_off = seg_off[lane];
-        if (lane < S && peers) lane_peer = peers[static_cast<int64_t>(lane) * n + row];
+        if (lane < S) lane_peer = partner_of(peers, shift, n, lane, row);
         const bool below = lane >= 1 && lane < S && lane_off <= c0;
         first_seg = __builtin_popcountll(__builtin_amdgcn_ballot_w64(below));
     } else {
@@ -737,42 +818,9 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
         if (sb < c0) sb = c0;
         if (se > c1) se = c1;
         if (sb >= se) continue;
-        int peer = row;
-        if (shift > 0) peer = row >= shift ? row - shift : row - shift + n;
-        else if (peers) peer = in_lanes ? __builtin_amdgcn_readlane(lane_peer, s)
-                                        : peers[static_cast<int64_t>(s) * n + row];
-        if (static_cast<unsigned>(peer) >= static_cast<unsigned>(n)) peer = row;
-
-        // `mine` holds (or will hold) this row's data; average it with the partner's and store.
-        // Operators with many rows behind a gossiping row (hierarchical groups) reduce their
-        // own rows before the partner's are requested, which halves the registers in flight.
-        auto mix_and_store = [&](auto full_c, const unsigned (&m)[U]) {
-            constexpr bool FULL = decltype(full_c)::value;
-            constexpr bool kOneAtATime = Op::kRawPerSlice * U >= 16;
-            typename Op::template Work<U> a, out;
-            if (skip_mix) {
-                op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
-                out = a;
-            } else {
-                typename Op::template Work<U> c;
-                if constexpr (kOneAtATime) {
-                    op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
-                    op.template issue<U, FULL, false>(peer, off, m, mine);
-                    op.template finish<U, FULL, NT, false>(peer, off, m, mine, c);
-                } else {
-                    typename Op::template Raw<U> theirs;
-                    op.template issue<U, FULL, false>(peer, off, m, theirs);
-                    op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
-                    op.template finish<U, FULL, NT, false>(peer, off, m, theirs, c);
-                }
-#pragma unroll
-                for (int u = 0; u < Op::template Work<U>::kN; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
-            }
-            op.template store<U, FULL, NT>(row, off, m, out);
-        };
-        if (whole && sb == c0 && se == c0 + kTileCols) {
-            // fast path: one segment covers the tile; `mine` is already on its way
-            mix_and_store(std::true_type{}, full_mask);
+        const int peer = in_lanes ? __builtin_amdgcn_readlane(lane_peer, s) : partner_of(peers, shift, n, s, row);
+        if (whole && sb == c0 && se == c0 + kTileCols) {  // one segment covers the whole tile
+            mix_and_store(std::true_type{}, full_mask, peer);
             return;
         }
         // boundary tile: per-element predication, once per overlapped segment
@@ -787,7 +835,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
             }
         }
         op.template issue<U, false, false>(row, off, mask, mine);
-        mix_and_store(std::false_type{}, mask);
+        mix_and_store(std::false_type{}, mask, peer);
     }
 }
 
@@ -899,12 +947,11 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     if (slot < 0) ordered = false;
     int64_t cl = cl_req;
     if (cl < 1) {
-        // ordered rows: a row visit of 512 KB per XCD, 256 KB for 16-bit rows (measured optima
-        // on MI355X: shorter visits lose DRAM row locality, longer ones push the previous visit
-        // out of L2);
+        // ordered rows: the operator's visit length per XCD (shorter visits lose DRAM row
+        // locality, longer ones push the previous visit out of L2);
         // natural row order: the whole cluster (all rows) should fit one XCD's 4 MB L2
         const int64_t row_bytes = chunk_cols * (16 / Op::kElems) * a.rows_per_gossip_row;
-        cl = ordered ? (Op::kElems == 8 ? (256 << 10) : (512 << 10)) / row_bytes : (4 << 20) / (row_bytes * a.n);
+        cl = ordered ? (static_cast<int64_t>(Op::kGather.visit_kb) << 10) / row_bytes : (4 << 20) / (row_bytes * a.n);
         if (cl < 1) cl = 1;
     }
     if (ordered) {                                // the order table must fit its slot
@@ -919,6 +966,8 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
         clusters = (nchunks + cl * nxcd - 1) / (cl * nxcd);
     }
     if (cl * nxcd > 0x7fffffffLL || clusters > 65535 || a.n > 65535) { *status = CX_ERR_SHAPE; return true; }
+    // the kernel numbers chunks and tiles, the grid's padding included, in 32 bits
+    if ((clusters * nxcd * cl + 1) * waves > 0x7fffffffLL) { *status = CX_ERR_SHAPE; return true; }
     if (clusters * nxcd * a.n > kOrderEntries) ordered = false;   // table too large: natural row order
     const dim3 grid(static_cast<unsigned>(cl * nxcd), static_cast<unsigned>(a.n),
                     static_cast<unsigned>(clusters));
@@ -933,10 +982,12 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     }
     if (nt)
         hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, 0, a.stream, op, a.n, a.P, a.S,
-                           a.seg_off, a.peers, a.shift, a.skip_mix, nchunks, static_cast<int>(cl), xcd_shift, slot);
+                           a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),
+                           static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, slot);
     else
         hipLaunchKernelGGL((gather_kernel<Op, U, false>), grid, block, 0, a.stream, op, a.n, a.P, a.S,
-                           a.seg_off, a.peers, a.shift, a.skip_mix, nchunks, static_cast<int>(cl), xcd_shift, slot);
+                           a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),
+                           static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, slot);
     *status = hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
     return true;
 }
@@ -948,11 +999,11 @@ int launch_mix(const Op &op, const MixArgs &a)
     if ((a.P + 255) / 256 > 0x7fffffffLL) return CX_ERR_SHAPE;
     if (a.out_of_place && cx_get_tuning(5) != 1) {
         int u = cx_get_tuning(0);
-        if (u != 1 && u != 2 && u != 4) u = 2;
+        if (u != 1 && u != 2 && u != 4) u = Op::kGather.U;
         while (u > 1 && Op::kRawPerSlice * u > 8) u >>= 1;   // the rows in flight must fit the registers
         if (Op::kRawPerSlice >= 8) u = 1;
         int waves = cx_get_tuning(1);
-        if (waves < 1 || waves > kMaxWavesPerBlock) waves = 4;
+        if (waves < 1 || waves > kMaxWavesPerBlock) waves = Op::kGather.waves;
         const int nt = cx_get_tuning(2) == 0 ? 0 : 1;
         const int cl = cx_get_tuning(6);
         const int xcd_aware = cx_get_tuning(7) == 0 ? 0 : 1;
