@@ -13,7 +13,7 @@ int cx_gossip_mix_bf16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_
     if (rc != CX_OK) return rc;
     const Bf16Op op{x_in, x_out, ld};
     const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream), x_in != x_out, 1};
-    return launch_mix<Bf16Op, 1, 2>(op, a);
+    return launch_mix<Bf16Op>(op, a);
 }
 
 }  // extern "C"

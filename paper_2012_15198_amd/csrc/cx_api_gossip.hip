@@ -38,7 +38,7 @@ int cx_gossip_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_
     if (rc != CX_OK) return rc;
     const MeanOp<1> op{x_in, x_out, ld, 1.0f};
     const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream), x_in != x_out, 1};
-    return launch_mix<MeanOp<1>, 4, 2>(op, a);
+    return launch_mix<MeanOp<1>>(op, a);
 }
 
 int cx_copy_baseline(const float *src, float *dst, int64_t n, void *stream)
@@ -47,7 +47,7 @@ int cx_copy_baseline(const float *src, float *dst, int64_t n, void *stream)
     if (n < 4 || (n & 3) != 0) return CX_ERR_SHAPE;
     if (misaligned(src) || misaligned(dst)) return CX_ERR_ALIGN;
     if (any_overlap(src, dst, static_cast<uint64_t>(n) * 4u)) return CX_ERR_ALIAS;
-    const Launch l = pick_launch(1, 2);
+    const Launch l = pick_launch(WalkShape{1, 2, 4, 0});
     const int64_t nslices = n / 4;
     const int64_t ntiles = (nslices + 64 * l.U - 1) / (64 * l.U);
     const int64_t nblocks = (ntiles + 3) / 4;

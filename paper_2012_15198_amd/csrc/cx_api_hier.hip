@@ -20,11 +20,11 @@ int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t 
     const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
     const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
     switch (G) {
-    case 1: return launch_mix<MeanOp<1>, 2, 4>(MeanOp<1>{x_in, x_out, ld, inv_g}, a);
-    case 2: return launch_mix<MeanOp<2>, 2, 4>(MeanOp<2>{x_in, x_out, ld, inv_g}, a);
-    case 4: return launch_mix<MeanOp<4>, 1, 4>(MeanOp<4>{x_in, x_out, ld, inv_g}, a);
-    case 8: return launch_mix<MeanOp<8>, 1, 4>(MeanOp<8>{x_in, x_out, ld, inv_g}, a);
-    case 16: return launch_mix<MeanOp<16>, 1, 2>(MeanOp<16>{x_in, x_out, ld, inv_g}, a);
+    case 1: return launch_mix<MeanOp<1>>(MeanOp<1>{x_in, x_out, ld, inv_g}, a);
+    case 2: return launch_mix<MeanOp<2>>(MeanOp<2>{x_in, x_out, ld, inv_g}, a);
+    case 4: return launch_mix<MeanOp<4>>(MeanOp<4>{x_in, x_out, ld, inv_g}, a);
+    case 8: return launch_mix<MeanOp<8>>(MeanOp<8>{x_in, x_out, ld, inv_g}, a);
+    case 16: return launch_mix<MeanOp<16>>(MeanOp<16>{x_in, x_out, ld, inv_g}, a);
     default: return CX_ERR_UNSUPPORTED;
     }
 }

@@ -35,10 +35,10 @@ int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, fl
     const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
     const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
     switch (G) {
-    case 1: return launch_mix<HierFusedOp<1>, 1, 4>(HierFusedOp<1>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 2: return launch_mix<HierFusedOp<2>, 1, 4>(HierFusedOp<2>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 4: return launch_mix<HierFusedOp<4>, 1, 4>(HierFusedOp<4>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 8: return launch_mix<HierFusedOp<8>, 1, 2>(HierFusedOp<8>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    case 1: return launch_mix<HierFusedOp<1>>(HierFusedOp<1>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    case 2: return launch_mix<HierFusedOp<2>>(HierFusedOp<2>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    case 4: return launch_mix<HierFusedOp<4>>(HierFusedOp<4>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    case 8: return launch_mix<HierFusedOp<8>>(HierFusedOp<8>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
     default: return CX_ERR_UNSUPPORTED;
     }
 }

@@ -36,7 +36,7 @@ int cx_pushsum_mix(const float *x_in, float *x_out, const float *w_in, float *w_
     if (hipGetLastError() != hipSuccess) return CX_ERR_HIP;
     const PushOp op{x_in, x_out, z_out, w_in, ld, W, hop};
     const MixArgs a{W, P, 1, /*seg_off: unused for S == 1*/ nullptr, nullptr, hop, 0, st, x_in != x_out, 1};
-    return launch_mix<PushOp, 2, 4>(op, a);
+    return launch_mix<PushOp>(op, a);
 }
 
 }  // extern "C"

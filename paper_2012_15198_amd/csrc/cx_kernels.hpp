@@ -18,7 +18,7 @@
 //     neighbouring chunks row after row; rows follow the cycles of the peer permutation,
 //     so a block's partner is the next block's own row).
 //   * Long contiguous row visits per XCD keep the DRAM row buffers busy, which a kernel
-//     whose waves each wander over all rows cannot do (measured: 75 % vs 67 % of peak).
+//     whose waves each wander over all rows cannot do (measured: 75 % vs 71 % of peak).
 //   * order_kernel, a few microseconds ahead of it, derives the row order from the
 //     device-resident peer table into library-owned device memory (no allocation): one word
 //     per (cluster, position) with the row, its partner and a "one segment covers this
@@ -153,10 +153,14 @@ __device__ __forceinline__ Tile<U> tree_sum(const Tile<U> *r)
 // Each operator splits "load gossiping row r" into issue() -- put the row's global loads in
 // flight into a Raw slot -- and finish() -- turn the arrived data into the tile that takes
 // part in the pairwise average.  kRawPerSlice = 16-byte registers per slice and slot.
-// kGather = the operator's default launch shape in the out-of-place kernel.
+// kGather = the operator's default launch shape in the out-of-place kernel, kWalk = in the
+// in-place kernel (measured optima on MI355X).
 struct GatherShape {
     int U, waves, visit_kb;
 };
+struct WalkShape {
+    int U, D, waves, wgs_per_cu;       // slices per lane, rows in flight, waves per workgroup,
+};                                     // resident workgroups per CU (0 = as many as fit)
 
 // Plain gossip (G == 1) and hierarchical mode (a gossiping row = a group of G rows).
 template <int G>
@@ -166,7 +170,10 @@ struct MeanOp {
     static constexpr int kRawPerSlice = G;
     // out-of-place launch: slices per lane, waves per workgroup, KB of one visit to a gossiping row
     // (all G rows behind it) per XCD -- measured optima on MI355X
-    static constexpr GatherShape kGather = G == 1 ? GatherShape{1, 4, 256} : GatherShape{1, 8, 1024};
+    static constexpr GatherShape kGather =
+        G == 1 ? GatherShape{1, 4, 256} : G <= 4 ? GatherShape{1, 8, 512} : GatherShape{1, 8, 1024};
+    static constexpr WalkShape kWalk =
+        G == 1 ? WalkShape{1, 2, 2, 8} : G == 2 ? WalkShape{2, 4, 2, 2} : G <= 8 ? WalkShape{1, 4, 2, 2} : WalkShape{1, 2, 2, 2};
     template <int U> struct Raw { Tile<U> r[G]; };
     const float *xin;
     float *xout;
@@ -206,6 +213,7 @@ struct FusedOp {
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = 3;
     static constexpr GatherShape kGather{1, 8, 256};   // out-of-place launch: slices, waves, row visit KB per XCD
+    static constexpr WalkShape kWalk{4, 2, 4, 2};
     template <int U> struct Raw { Tile<U> x, v, g; };
     const float *xin;
     float *xout;
@@ -251,7 +259,10 @@ struct HierFusedOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = G + 2;
-    static constexpr GatherShape kGather{1, 8, 1024};  // out-of-place launch: slices, waves, group visit KB per XCD
+    // out-of-place launch: slices, waves, group visit KB per XCD
+    static constexpr GatherShape kGather =
+        G == 1 ? GatherShape{1, 8, 256} : G <= 4 ? GatherShape{1, 8, 512} : GatherShape{1, 8, 1024};
+    static constexpr WalkShape kWalk = G <= 4 ? WalkShape{1, 4, 2, 2} : WalkShape{1, 2, 2, 2};
     template <int U> struct Raw { Tile<U> g[G], x, v; };
     const float *xin;
     float *xout;
@@ -347,6 +358,7 @@ struct Row16Op {
     template <int U> using Work = Tile<2 * U>;             // 8 fp32 values per slice
     static constexpr int kRawPerSlice = 1;
     static constexpr GatherShape kGather{2, 8, 128};   // out-of-place launch: slices, waves, row visit KB per XCD
+    static constexpr WalkShape kWalk{1, 2, 8, 0};
     template <int U> struct Raw { Tile<U> x; };            // packed 16-bit pairs, as loaded
     const uint16_t *xin;
     uint16_t *xout;
@@ -404,6 +416,7 @@ struct PushOp {
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = 1;
     static constexpr GatherShape kGather{2, 4, 512};   // out-of-place launch: slices, waves, row visit KB per XCD
+    static constexpr WalkShape kWalk{2, 2, 8, 2};
     template <int U> struct Raw { Tile<U> x; };
     const float *xin;
     float *xout;
@@ -843,21 +856,23 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
 // Host side
 // ---------------------------------------------------------------------------------
 struct Launch {
-    int U, D, waves, nt, lockstep;
+    int U, D, waves, nt, lockstep, wgs_per_cu;
 };
 
-Launch pick_launch(int default_u, int default_d)
+Launch pick_launch(const WalkShape &dflt)
 {
     Launch l;
     l.U = cx_get_tuning(0);
-    if (l.U != 1 && l.U != 2 && l.U != 4) l.U = default_u;
+    if (l.U != 1 && l.U != 2 && l.U != 4) l.U = dflt.U;
     l.lockstep = cx_get_tuning(4) == 0 ? 0 : 1;
     l.waves = cx_get_tuning(1);
-    if (l.waves < 1 || l.waves > kMaxWavesPerBlock) l.waves = l.lockstep ? 8 : 4;
+    if (l.waves < 1 || l.waves > kMaxWavesPerBlock) l.waves = dflt.waves;
     l.nt = cx_get_tuning(2);
     if (l.nt != 0 && l.nt != 1) l.nt = 1;
     l.D = cx_get_tuning(3);
-    if (l.D != 2 && l.D != 4 && l.D != 8) l.D = default_d;
+    if (l.D != 2 && l.D != 4 && l.D != 8) l.D = dflt.D;
+    l.wgs_per_cu = cx_get_tuning(9);
+    if (l.wgs_per_cu < 0 || l.wgs_per_cu > 16) l.wgs_per_cu = dflt.wgs_per_cu;
     return l;
 }
 
@@ -908,7 +923,15 @@ bool try_launch(const Op &op, const Launch &l, const MixArgs &a)
         while (waves > 1 && sizeof(int) * 2 * static_cast<size_t>(a.n) * waves > 48 * 1024) --waves;
         const int64_t nblocks = (ntiles + waves - 1) / waves;
         const dim3 grid(static_cast<unsigned>(nblocks)), block(kWave * waves);
-        const size_t lds = sizeof(int) * 2 * static_cast<size_t>(a.n) * waves;
+        size_t lds = sizeof(int) * 2 * static_cast<size_t>(a.n) * waves;
+        if (l.wgs_per_cu > 0) {
+            // Fewer resident workgroups keep fewer bytes in flight per CU, which this memory
+            // system rewards for the row-wandering walk (+3 to +8 %).  The cap is an LDS
+            // reservation: a CU has 160 KB, a workgroup may take up to 64 KB.
+            size_t reserve = (160u << 10) / static_cast<unsigned>(l.wgs_per_cu);
+            if (reserve > (64u << 10)) reserve = 64u << 10;
+            if (lds < reserve) lds = reserve;
+        }
         if (l.nt)
             hipLaunchKernelGGL((mix_kernel<Op, U, D, true>), grid, block, lds, a.stream, op, a.n, a.P,
                                a.S, a.seg_off, a.peers, a.shift, a.skip_mix, ntiles, l.lockstep);
@@ -992,9 +1015,10 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     return true;
 }
 
-template <class Op, int U0, int D0>
+template <class Op>
 int launch_mix(const Op &op, const MixArgs &a)
 {
+    constexpr int U0 = Op::kWalk.U, D0 = Op::kWalk.D;
     static_assert(fits<Op, U0, D0>(), "default launch shape must fit");
     if ((a.P + 255) / 256 > 0x7fffffffLL) return CX_ERR_SHAPE;
     if (a.out_of_place && cx_get_tuning(5) != 1) {
@@ -1013,7 +1037,7 @@ int launch_mix(const Op &op, const MixArgs &a)
             try_gather<Op, 4>(op, u, waves, nt, cl, xcd_aware, a, &status))
             return status;
     }
-    Launch l = pick_launch(U0, D0);
+    Launch l = pick_launch(Op::kWalk);
     const bool done =
         try_launch<Op, 1, 2>(op, l, a) || try_launch<Op, 1, 4>(op, l, a) || try_launch<Op, 1, 8>(op, l, a) ||
         try_launch<Op, 2, 2>(op, l, a) || try_launch<Op, 2, 4>(op, l, a) || try_launch<Op, 2, 8>(op, l, a) ||
