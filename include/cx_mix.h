@@ -235,7 +235,7 @@ int cx_gossip_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t
  *   key 5: 1 = use the in-place kernel for out-of-place calls too
  *   key 6: out of place: chunks per cluster (1..4096)     key 7: out of place: XCD-aware block order (0/1)
  *   key 8: out of place: rows ordered along the permutation cycles (0/1)
- *   key 9: in place: resident workgroups per CU (1..16; 0 = as many as fit)
+ *   key 9: resident workgroups per CU, both kernels (1..16; 0 = as many as fit)
  * A (key 0, key 3) pair that an operator was not built with falls back to its default.
  * cx_set_tuning returns CX_ERR_SHAPE for an unknown key or value; a value of -1 restores
  * the default.

@@ -156,8 +156,8 @@ __device__ __forceinline__ Tile<U> tree_sum(const Tile<U> *r)
 // kGather = the operator's default launch shape in the out-of-place kernel, kWalk = in the
 // in-place kernel (measured optima on MI355X).
 struct GatherShape {
-    int U, waves, visit_kb;
-};
+    int U, waves, visit_kb, wgs_per_cu;   // slices per lane, waves per workgroup, KB of one row visit
+};                                        // per XCD, resident workgroups per CU (0 = as many as fit)
 struct WalkShape {
     int U, D, waves, wgs_per_cu;       // slices per lane, rows in flight, waves per workgroup,
 };                                     // resident workgroups per CU (0 = as many as fit)
@@ -171,7 +171,7 @@ struct MeanOp {
     // out-of-place launch: slices per lane, waves per workgroup, KB of one visit to a gossiping row
     // (all G rows behind it) per XCD -- measured optima on MI355X
     static constexpr GatherShape kGather =
-        G == 1 ? GatherShape{1, 4, 256} : G <= 4 ? GatherShape{1, 8, 512} : GatherShape{1, 8, 1024};
+        G == 1 ? GatherShape{1, 4, 256, 0} : G <= 4 ? GatherShape{1, 8, 512, 0} : GatherShape{1, 8, 1024, 0};
     static constexpr WalkShape kWalk =
         G == 1 ? WalkShape{1, 2, 2, 8} : G == 2 ? WalkShape{2, 4, 2, 2} : G <= 8 ? WalkShape{1, 4, 2, 2} : WalkShape{1, 2, 2, 2};
     template <int U> struct Raw { Tile<U> r[G]; };
@@ -212,7 +212,7 @@ struct FusedOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = 3;
-    static constexpr GatherShape kGather{1, 8, 256};   // out-of-place launch: slices, waves, row visit KB per XCD
+    static constexpr GatherShape kGather{1, 8, 256, 3};
     static constexpr WalkShape kWalk{4, 2, 4, 2};
     template <int U> struct Raw { Tile<U> x, v, g; };
     const float *xin;
@@ -261,7 +261,7 @@ struct HierFusedOp {
     static constexpr int kRawPerSlice = G + 2;
     // out-of-place launch: slices, waves, group visit KB per XCD
     static constexpr GatherShape kGather =
-        G == 1 ? GatherShape{1, 8, 256} : G <= 4 ? GatherShape{1, 8, 512} : GatherShape{1, 8, 1024};
+        G == 1 ? GatherShape{1, 8, 256, 0} : G <= 4 ? GatherShape{1, 8, 512, 0} : GatherShape{1, 8, 1024, 0};
     static constexpr WalkShape kWalk = G <= 4 ? WalkShape{1, 4, 2, 2} : WalkShape{1, 2, 2, 2};
     template <int U> struct Raw { Tile<U> g[G], x, v; };
     const float *xin;
@@ -357,7 +357,7 @@ struct Row16Op {
     static constexpr int kElems = 8;                       // 16-bit columns per 16-byte slice
     template <int U> using Work = Tile<2 * U>;             // 8 fp32 values per slice
     static constexpr int kRawPerSlice = 1;
-    static constexpr GatherShape kGather{2, 8, 128};   // out-of-place launch: slices, waves, row visit KB per XCD
+    static constexpr GatherShape kGather{2, 8, 128, 0};
     static constexpr WalkShape kWalk{1, 2, 8, 0};
     template <int U> struct Raw { Tile<U> x; };            // packed 16-bit pairs, as loaded
     const uint16_t *xin;
@@ -415,7 +415,7 @@ struct PushOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
     template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
     static constexpr int kRawPerSlice = 1;
-    static constexpr GatherShape kGather{2, 4, 512};   // out-of-place launch: slices, waves, row visit KB per XCD
+    static constexpr GatherShape kGather{2, 4, 512, 0};
     static constexpr WalkShape kWalk{2, 2, 8, 2};
     template <int U> struct Raw { Tile<U> x; };
     const float *xin;
@@ -902,6 +902,17 @@ struct MixArgs {
     int rows_per_gossip_row;    // G: matrix rows behind one gossiping row (cluster footprint)
 };
 
+// Dynamic LDS a workgroup reserves so that at most `wgs_per_cu` of them are resident on a CU
+// (0 = no cap).  Fewer resident workgroups keep fewer bytes in flight per CU, which this
+// memory system rewards for the row-wandering walk (+3 to +8 %) and for the fused gather
+// (+2 %).  A CU has 160 KB of LDS; a workgroup may take up to 64 KB.
+[[maybe_unused]] size_t lds_reservation(int wgs_per_cu)
+{
+    if (wgs_per_cu <= 0) return 0;
+    const size_t reserve = (160u << 10) / static_cast<unsigned>(wgs_per_cu);
+    return reserve > (64u << 10) ? (64u << 10) : reserve;
+}
+
 // A (slices, depth) pair is built for an operator only if its ring of in-flight rows stays
 // within the register file without spilling (at least two waves per SIMD stay resident).
 template <class Op, int U, int D>
@@ -924,14 +935,7 @@ bool try_launch(const Op &op, const Launch &l, const MixArgs &a)
         const int64_t nblocks = (ntiles + waves - 1) / waves;
         const dim3 grid(static_cast<unsigned>(nblocks)), block(kWave * waves);
         size_t lds = sizeof(int) * 2 * static_cast<size_t>(a.n) * waves;
-        if (l.wgs_per_cu > 0) {
-            // Fewer resident workgroups keep fewer bytes in flight per CU, which this memory
-            // system rewards for the row-wandering walk (+3 to +8 %).  The cap is an LDS
-            // reservation: a CU has 160 KB, a workgroup may take up to 64 KB.
-            size_t reserve = (160u << 10) / static_cast<unsigned>(l.wgs_per_cu);
-            if (reserve > (64u << 10)) reserve = 64u << 10;
-            if (lds < reserve) lds = reserve;
-        }
+        if (lds < lds_reservation(l.wgs_per_cu)) lds = lds_reservation(l.wgs_per_cu);
         if (l.nt)
             hipLaunchKernelGGL((mix_kernel<Op, U, D, true>), grid, block, lds, a.stream, op, a.n, a.P,
                                a.S, a.seg_off, a.peers, a.shift, a.skip_mix, ntiles, l.lockstep);
@@ -1003,12 +1007,15 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
                            a.S, a.seg_off, a.peers, a.shift, cl * chunk_cols, static_cast<int>(nclusters), slot);
         if (hipGetLastError() != hipSuccess) { *status = CX_ERR_HIP; return true; }
     }
+    int cap = cx_get_tuning(9);
+    if (cap < 0 || cap > 16) cap = Op::kGather.wgs_per_cu;
+    const size_t glds = lds_reservation(cap);
     if (nt)
-        hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, 0, a.stream, op, a.n, a.P, a.S,
+        hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, glds, a.stream, op, a.n, a.P, a.S,
                            a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),
                            static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, slot);
     else
-        hipLaunchKernelGGL((gather_kernel<Op, U, false>), grid, block, 0, a.stream, op, a.n, a.P, a.S,
+        hipLaunchKernelGGL((gather_kernel<Op, U, false>), grid, block, glds, a.stream, op, a.n, a.P, a.S,
                            a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),
                            static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, slot);
     *status = hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
