@@ -357,6 +357,27 @@ def test_gossip_f16_all_pairs_of_a_pattern_sample():
     assert same_f16(host(out).view(np.uint16)[:, :P], want[:, :P])
 
 
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_16bit_every_pattern_against_three_partners(fmt):
+    # rows: all 65536 patterns; the same reversed; a constant; rotated by 12345: every pattern
+    # meets itself-reversed, a fixed partner and a far one
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    x = np.stack([h, h[::-1], np.full_like(h, 0x3C01 if fmt == "f16" else 0x3F81), np.roll(h, 12345)])
+    P = h.size
+    so = WL.equal_seg_off(P, 3)
+    pe = np.array([[1, 2, 3, 0], [3, 0, 1, 2], [2, 3, 0, 1]], dtype=np.int32)
+    mix, omix, same = ((cx.cx_gossip_mix_f16, O.gossip_mix_f16, same_f16) if fmt == "f16" else
+                       (cx.cx_gossip_mix_bf16, O.gossip_mix_bf16, same_bf16))
+    with np.errstate(all="ignore"):
+        want = omix(x, P, so, pe)
+    xd = dev(x.view(np.int16))
+    out = torch.empty_like(xd)
+    mix(xd, out, P, dev(so), dev(pe))
+    mix(xd, xd, P, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    assert same(host(out).view(np.uint16), want) and same(host(xd).view(np.uint16), want)
+
+
 # ------------------------------------------------------------------------ hierarchical
 def hier_tol(x, G, P, y64, pe, so):
     """1e-6 relative to max(|ref|, mean |x| over the rows that enter the result)."""

@@ -476,3 +476,21 @@ def test_f16_mix_hand_case_and_agreement_with_the_fp32_mix():
         assert (ex.astype(np.float16).view(np.uint16) == yh[:, lo:hi]).all()
     same = np.tile(xh[:1], (W, 1))
     assert (O.gossip_mix_f16(same, P, so, pe) == same).all()
+
+
+def test_16bit_identical_rows_are_a_fixed_point_for_every_bit_pattern():
+    # (a + a) * 0.5 == a exactly: doubling and halving are exact in fp32 for every binary16 value
+    # (subnormals and the largest finite value included) and for every bfloat16 value below 2^127
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    P = h.size
+    pe = np.array([[1, 2, 0]], dtype=np.int32)
+    f16_ok = ~np.isnan(h.view(np.float16))
+    x = np.tile(h, (3, 1))
+    y = O.gossip_mix_f16(x, P, [0, P], pe)
+    assert (y[:, f16_ok] == x[:, f16_ok]).all()
+    bf = O.bf16_to_f32(h)
+    bf_ok = ~np.isnan(bf) & (np.abs(bf) < 2.0 ** 127)
+    y = O.gossip_mix_bf16(x, P, [0, P], pe)
+    assert (y[:, bf_ok] == x[:, bf_ok]).all()
+    big = np.isfinite(bf) & (np.abs(bf) >= 2.0 ** 127)           # a + a overflows fp32: infinity
+    assert (O.bf16_to_f32(y[0, big]) == np.sign(bf[big]) * np.inf).all()
