@@ -170,3 +170,49 @@ def test_tuning_keys():
         assert cx.cx_get_tuning(key) == -1
     with pytest.raises(cx.CxError):
         cx.cx_set_tuning(10, 1)
+
+
+def test_header_is_plain_c_and_a_c_program_can_call_the_host_half(tmp_path):
+    """include/cx_mix.h compiles as C99 with -pedantic, and a C program linked against the
+    library generates a table and has it checked (host entry points only: no GPU needed)."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.join(root, "paper_2012_15198_amd")
+    src = tmp_path / "use_cx.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <stdlib.h>
+#include "cx_mix.h"
+int main(void)
+{
+    enum { N = 8, S = 3, R = 2 };
+    int32_t peers[R * S * N];
+    int64_t seg_off[S + 1] = {0, 10, 20, 30};
+    int r, s, i, rc;
+    if (cx_abi_version() < 1) return 10;
+    rc = cx_topology_gen(2u, N, S, 0, R, CX_TOPO_FAIR, peers);
+    if (rc != CX_OK) return 11;
+    for (r = 0; r < R; ++r)
+        if (cx_check_peers(peers + r * S * N, S, N) != CX_OK) return 12;
+    if (cx_check_segments(seg_off, S, 30) != CX_OK) return 13;
+    if (cx_check_segments(seg_off, S, 31) != CX_ERR_SEGMENTS) return 14;
+    if (cx_gossip_mix(NULL, NULL, 32, N, 30, S, NULL, NULL, 0u, NULL) != CX_ERR_NULL) return 15;
+    for (s = 0; s < S; ++s) {
+        for (i = 0; i < N; ++i) printf("%d ", (int)peers[s * N + i]);
+        printf("\n");
+    }
+    puts(cx_status_string(CX_ERR_PEERS));
+    return 0;
+}
+''')
+    exe = tmp_path / "use_cx"
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                           "-I", os.path.join(root, "include"), str(src), "-o", str(exe),
+                           "-L", libdir, "-lcxmix", "-Wl,-rpath," + libdir])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, (out.returncode, out.stderr)
+    rows = out.stdout.strip().split("\n")
+    want = cx.cx_topology_gen(2, 8, 3, 0, 1)[0]
+    assert [list(map(int, r.split())) for r in rows[:3]] == want.tolist()
+    assert rows[3] == cx.cx_status_string(-4)
