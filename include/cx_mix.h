@@ -34,7 +34,7 @@
  *              in place, one wavefront owns a column tile and walks the rows along the
  *              cycles of the peer permutation; out of place, one short workgroup per
  *              (row, column chunk) reads the row and its peer and writes the result --
- *              the faster of the two on MI355X (about 74 % against about 66 % of the HBM
+ *              the faster of the two on MI355X (about 75 % against about 71 % of the HBM
  *              peak on a 32 x 25.6M matrix).
  *   peer table in place, each peers[s] must be a permutation of 0..n-1: a segment whose
  *              table is not one is left unmixed (treated as the identity).  Out of place,
