@@ -27,8 +27,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
-def describe(wl) -> str:
-    s = f"{wl.name}: W={wl.W} P={wl.P} fp32 S={wl.S}"
+def describe(wl, rows="fp32") -> str:
+    s = f"{wl.name}: W={wl.W} P={wl.P} {rows} S={wl.S}"
     if wl.G > 1:
         s += f" hierarchical G={wl.G} L={wl.L}"
     if wl.layers:
@@ -263,7 +263,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": f"{rows16} rows, f32 arithmetic" if rows16 else "f32",
         "data": "synthetic",
-        "config": {"workload": describe(wl) if kind != "gossip" or wl.G == 1 else describe(wl) + " (flat gossip over all rows)",
+        "config": {"workload": describe(wl, rows16 or "fp32") if kind != "gossip" or wl.G == 1
+                   else describe(wl, rows16 or "fp32") + " (flat gossip over all rows)",
                    "entry_point": {"fused": "cx_sgd_fused_mix", "hiersgd": "cx_hier_sgd_fused_mix"}.get(
                        kind, f"cx_{kind}_mix" + ("_" + rows16 if rows16 else "")),
                    "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
