@@ -49,7 +49,9 @@
  *              allocates.  A slot is bound to the stream that first uses it; calls on one
  *              stream run in order, so a table is never rewritten while it is read.  Calls
  *              of one entry point on a fifth and later stream run without the table: same
- *              results, lower speed.
+ *              results, lower speed.  A call captured into a HIP graph keeps the slot of the
+ *              stream it was captured on: replay the graph on that stream, or at least never
+ *              while other calls of the same entry point run on it.
  *   limits     at most CX_MAX_ROWS gossiping rows (W, or W/G in hierarchical mode).
  *   return     CX_OK (0) or a negative cx_status.  Argument errors are detected on the host
  *              before anything is enqueued.
