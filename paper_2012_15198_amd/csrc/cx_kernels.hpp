@@ -43,7 +43,8 @@
 //  PushOp / Row16Op) say what loading and storing a "gossiping row" means: the pairwise-tree
 //  mean of a group of G rows, the momentum-SGD update applied on the way in (to the row or
 //  to a group leader fed with the group's mean gradient), the push-sum de-biasing, or the
-//  bfloat16 unpacking and rounding.
+//  unpacking and rounding of 16-bit rows (bfloat16, binary16).  Each operator also names its
+//  measured launch shapes (kGather, kWalk).
 #ifndef CX_KERNELS_HPP
 #define CX_KERNELS_HPP
 #include "cx_mix.h"
