@@ -24,8 +24,9 @@
  * conservation; the halving of the deviation norm at W=3; G=W equals the plain
  * column mean; log2(W) exponential hops equal the exact mean; the fused update
  * with mixing off equals torch.optim.SGD; the gradient-reducing hierarchical step
- * with one group equals SGD on the averaged gradient.  No function here is
- * "parity unpinned".
+ * with one group equals SGD on the averaged gradient; the bfloat16 and binary16
+ * conversions against torch's and numpy's on every bit pattern, their rounding
+ * ties, underflow and overflow by hand.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
