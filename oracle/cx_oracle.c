@@ -345,6 +345,69 @@ int oracle_hier_mix_f32(const float *x_in, float *x_out, int64_t ld, int32_t W, 
 }
 
 /* ------------------------------------------------------------------------- */
+/* The hierarchical step on 16-bit rows (fmt 0 = bfloat16, 1 = binary16): every */
+/* value is widened exactly, the step runs as above, and each result is rounded */
+/* ONCE to the 16-bit format.  Reference mode returns the unrounded doubles.    */
+/* ------------------------------------------------------------------------- */
+static float widen16(int fmt, uint16_t h) { return fmt ? oracle_f16_to_f32(h) : oracle_bf16_to_f32(h); }
+static uint16_t narrow16(int fmt, float f) { return fmt ? oracle_f32_to_f16(f) : oracle_f32_to_bf16(f); }
+
+int oracle_hier_mix16_f64(int fmt, const uint16_t *x_in, double *y_out, int64_t ld, int32_t W,
+                          int64_t P, int32_t G, int32_t S, const int64_t *seg_off,
+                          const int32_t *leader_peers)
+{
+    (void)P;
+    int32_t L = W / G;
+    double *m = (double *)malloc(sizeof(double) * (size_t)L);
+    if (!m) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t g = 0; g < L; ++g) {
+                double sum = 0.0;
+                for (int32_t j = 0; j < G; ++j)
+                    sum += (double)widen16(fmt, x_in[((int64_t)g * G + j) * ld + c]);
+                m[g] = sum / (double)G;
+            }
+            for (int32_t g = 0; g < L; ++g) {
+                double y = m[g];
+                if (L > 1) y = (m[g] + m[leader_peers[(int64_t)s * L + g]]) * 0.5;
+                for (int32_t j = 0; j < G; ++j)
+                    y_out[((int64_t)g * G + j) * ld + c] = y;
+            }
+        }
+    free(m);
+    return 0;
+}
+
+int oracle_hier_mix16_f32(int fmt, const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W,
+                          int64_t P, int32_t G, int32_t S, const int64_t *seg_off,
+                          const int32_t *leader_peers)
+{
+    (void)P;
+    int32_t L = W / G;
+    float inv_g = 1.0f / (float)G;
+    float *m = (float *)malloc(sizeof(float) * (size_t)L);
+    float *col = (float *)malloc(sizeof(float) * (size_t)W);
+    if (!m || !col) { free(m); free(col); return -2; }
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t i = 0; i < W; ++i) col[i] = widen16(fmt, x_in[(int64_t)i * ld + c]);
+            for (int32_t g = 0; g < L; ++g)
+                m[g] = tree_sum_f32(col + (int64_t)g * G, 1, G) * inv_g;
+            for (int32_t g = 0; g < L; ++g) {
+                float y = m[g];
+                if (L > 1) y = (m[g] + m[leader_peers[(int64_t)s * L + g]]) * 0.5f;
+                uint16_t r = narrow16(fmt, y);
+                for (int32_t j = 0; j < G; ++j)
+                    x_out[((int64_t)g * G + j) * ld + c] = r;
+            }
+        }
+    free(m);
+    free(col);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Local momentum-SGD step, then Algorithm 1's averaging on the updated       */
 /* parameters (Section 3.1: averaging happens after the gradient is applied): */
 /*     g' = g + wd*x ;  v' = mu*v + g' ;  x_half = x - lr*v'                  */

@@ -23,7 +23,7 @@ __all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topo
            "gossip_mix", "hier_mix_f64", "hier_mix_f32", "sgd_fused_mix_f64",
            "sgd_fused_mix_f32", "pushsum_mix_f64", "pushsum_mix_f32",
            "hier_sgd_fused_mix_f64", "hier_sgd_fused_mix_f32", "gossip_mix_bf16", "f32_to_bf16",
-           "bf16_to_f32", "gossip_mix_f16", "f32_to_f16", "f16_to_f32"]
+           "bf16_to_f32", "gossip_mix_f16", "f32_to_f16", "f16_to_f32", "hier_mix16_f64", "hier_mix16_f32"]
 
 
 def build_oracle(force: bool = False) -> str:
@@ -63,6 +63,8 @@ def _L():
         lib.oracle_f16_to_f32.restype = f32
         lib.oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
         lib.oracle_hier_mix_f64.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp]
+        lib.oracle_hier_mix16_f64.argtypes = [i32, vp, vp, i64, i32, i64, i32, i32, vp, vp]
+        lib.oracle_hier_mix16_f32.argtypes = [i32, vp, vp, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_hier_mix_f32.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_sgd_fused_mix_f64.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32,
                                                  i64, i32, i64, i32, vp, vp]
@@ -292,3 +294,33 @@ def f16_to_f32(h) -> np.ndarray:
 def gossip_mix_f16(x, P, seg_off, peers) -> np.ndarray:
     """x: uint16 [W][ld] of binary16 bit patterns; returns the mixed patterns."""
     return _mix16(_L().oracle_gossip_mix_f16, "gossip_mix_f16", x, P, seg_off, peers)
+
+
+_FMT = {"bf16": 0, "f16": 1}
+
+
+def _hier16(fn, fmt, x, out, P, G, seg_off, leader_peers):
+    W, ld = x.shape
+    if G < 1 or W % G:
+        raise ValueError("G must divide W")
+    L = W // G
+    so = _seg(seg_off, P)
+    S = len(so) - 1
+    pe = _peers(leader_peers, S, L) if L > 1 else None
+    _check(fn(_FMT[fmt], _p(x), _p(out), ld, W, P, G, S, _p(so), _p(pe)), "hier_mix16")
+    return out
+
+
+def hier_mix16_f64(fmt, x, P, G, seg_off, leader_peers) -> np.ndarray:
+    """Hierarchical step on 16-bit rows ("bf16" or "f16" bit patterns), exact widening, double
+    arithmetic, NOT rounded back: float64 [W][ld]."""
+    x = _mat(x, dtype=np.uint16)
+    widened = bf16_to_f32(x) if fmt == "bf16" else f16_to_f32(x)
+    return _hier16(_L().oracle_hier_mix16_f64, fmt, x, widened.astype(np.float64), P, G, seg_off, leader_peers)
+
+
+def hier_mix16_f32(fmt, x, P, G, seg_off, leader_peers) -> np.ndarray:
+    """The same in fp32 with the fixed pairwise-tree order and one rounding to the 16-bit
+    format: uint16 [W][ld]."""
+    x = _mat(x, dtype=np.uint16)
+    return _hier16(_L().oracle_hier_mix16_f32, fmt, x, x.copy(), P, G, seg_off, leader_peers)

@@ -494,3 +494,51 @@ def test_16bit_identical_rows_are_a_fixed_point_for_every_bit_pattern():
     assert (y[:, bf_ok] == x[:, bf_ok]).all()
     big = np.isfinite(bf) & (np.abs(bf) >= 2.0 ** 127)           # a + a overflows fp32: infinity
     assert (O.bf16_to_f32(y[0, big]) == np.sign(bf[big]) * np.inf).all()
+
+
+def _ulp16(fmt, y):
+    """Spacing of the 16-bit format at |y| (normal range)."""
+    bits = 8 if fmt == "bf16" else 11
+    e = np.floor(np.log2(np.maximum(np.abs(y), 2.0 ** -14)))
+    return 2.0 ** (e - (bits - 1))
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_hier16_hand_case_special_cases_and_reference(fmt):
+    widen, narrow, mix = ((O.bf16_to_f32, O.f32_to_bf16, O.gossip_mix_bf16) if fmt == "bf16" else
+                          (O.f16_to_f32, O.f32_to_f16, O.gossip_mix_f16))
+    # hand case, G=2, two groups: means 1.5 and -3.25, leader average -0.875 (exact in both formats)
+    x = narrow(np.array([[1.0, 4.0], [2.0, 0.0], [-3.0, 8.0], [-3.5, 4.0]], dtype=np.float32))
+    y = O.hier_mix16_f32(fmt, x, 2, 2, [0, 2], [[1, 0]])
+    assert widen(y).tolist() == [[-0.875, 4.0]] * 4
+    # the final rounding: binary16 group means 1 + 2^-9 and 1 average to 1 + 2^-10, which it holds exactly;
+    # bfloat16 group means 1.00390625 and 1 average to 1.001953125, which rounds to 1.0
+    x = narrow(np.array([[1.0], [1.0 + 2 ** -8], [1.0], [1.0]], dtype=np.float32)) if fmt == "f16" else \
+        narrow(np.array([[1.0], [1.0078125], [1.0], [1.0]], dtype=np.float32))
+    y = O.hier_mix16_f32(fmt, x, 1, 2, [0, 1], [[1, 0]])
+    want = 1.0 + 2 ** -10 if fmt == "f16" else 1.0       # bf16: (1.00390625 + 1)/2 = 1.001953125 -> 1.0
+    assert widen(y).ravel().tolist() == [want] * 4
+
+    W, P, S = 12, 257, 3
+    x = narrow(WL.gen_matrix(W, P, 1.0, 41))
+    so = WL.equal_seg_off(P, S)
+    # G = 1 is the plain 16-bit gossip, bit for bit
+    pe = O.topology(41, W, S, 0, 1)[0]
+    assert (O.hier_mix16_f32(fmt, x, P, 1, so, pe) == mix(x, P, so, pe)).all()
+    for G in (2, 3, 4, 6):
+        L = W // G
+        pe = O.topology(42, L, S, 0, 1)[0]
+        got = O.hier_mix16_f32(fmt, x, P, G, so, pe)
+        # the definition spelled with the pinned pieces: widen, fp32 hierarchical step, one rounding
+        assert (got == narrow(O.hier_mix_f32(widen(x), P, G, so, pe))).all()
+        # within half a 16-bit ulp (plus the fp32 tree's own error) of the exact double result
+        y64 = O.hier_mix16_f64(fmt, x, P, G, so, pe)
+        err = np.abs(widen(got).astype(np.float64) - y64)
+        assert (err <= 0.5 * _ulp16(fmt, y64) * (1 + 2.0 ** -9) + 2.0 ** -21).all()
+        # members of a group hold the same value; the reference equals the fp32-row reference on widened rows
+        assert (got.reshape(L, G, P) == got.reshape(L, G, P)[:, :1]).all()
+        assert (y64 == O.hier_mix_f64(widen(x), P, G, so, pe)).all()
+    # one group: every row is the rounded column mean
+    y = O.hier_mix16_f32(fmt, x, P, W, so, None)
+    mean = widen(x).astype(np.float64).mean(0)
+    assert (np.abs(widen(y).astype(np.float64) - mean) <= 0.5 * _ulp16(fmt, mean) * (1 + 2.0 ** -9) + 2.0 ** -21).all()
