@@ -96,6 +96,9 @@ class Runner:
             mix16(self.x, self.y, wl.P, self.so, tab)
         elif self.kind == "gossip":
             cx.cx_gossip_mix(self.x, self.y, wl.P, self.so, tab)
+        elif self.kind == "hier" and self.rows16:
+            mix16 = cx.cx_hier_mix_bf16 if self.rows16 == "bf16" else cx.cx_hier_mix_f16
+            mix16(self.x, self.y, wl.P, wl.G, self.so, tab)
         elif self.kind == "hier":
             cx.cx_hier_mix(self.x, self.y, wl.P, wl.G, self.so, tab)
         elif self.kind == "fused":
@@ -233,8 +236,8 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads' entry points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy", action="store_true")
-    ap.add_argument("--bf16", action="store_true", help="bfloat16 rows (gossip only): cx_gossip_mix_bf16")
-    ap.add_argument("--f16", action="store_true", help="binary16 rows (gossip only): cx_gossip_mix_f16")
+    ap.add_argument("--bf16", action="store_true", help="bfloat16 rows: cx_gossip_mix_bf16 / cx_hier_mix_bf16")
+    ap.add_argument("--f16", action="store_true", help="binary16 rows: cx_gossip_mix_f16 / cx_hier_mix_f16")
     ap.add_argument("--in-place", action="store_true",
                     help="update the matrix in place (cycle-walk kernel) instead of ping-pong buffers")
     args = ap.parse_args()
@@ -253,8 +256,8 @@ def main():
     if args.bf16 and args.f16:
         sys.exit("bench.py: --bf16 and --f16 exclude each other")
     rows16 = "bf16" if args.bf16 else "f16" if args.f16 else None
-    if rows16 and kind != "gossip":
-        sys.exit("bench.py: --bf16 / --f16 are available for the gossip entry point only")
+    if rows16 and kind not in ("gossip", "hier"):
+        sys.exit("bench.py: --bf16 / --f16 are available for the gossip and hierarchical entry points only")
     runner = Runner(wl, kind, args.steps + args.warmup, in_place=args.in_place, rows16=rows16)
     res = runner.run(args.steps, args.warmup)
     out = {

@@ -353,36 +353,71 @@ __device__ __forceinline__ void tile_store16(uint16_t *p, const unsigned (&mask)
     }
 }
 
-template <bool IEEE_HALF>
+// G == 1: plain gossip on 16-bit rows.  G > 1: hierarchical mode, a gossiping row = a group of
+// G rows whose widened values are tree-summed in fp32, scaled by 1/G, averaged between leaders
+// and rounded once on the way out.
+template <bool IEEE_HALF, int G = 1>
 struct Row16Op {
     static constexpr int kElems = 8;                       // 16-bit columns per 16-byte slice
     template <int U> using Work = Tile<2 * U>;             // 8 fp32 values per slice
-    static constexpr int kRawPerSlice = 1;
-    static constexpr GatherShape kGather{2, 8, 128, 0};
-    static constexpr WalkShape kWalk{1, 2, 8, 0};
-    template <int U> struct Raw { Tile<U> x; };            // packed 16-bit pairs, as loaded
+    static constexpr int kRawPerSlice = G;
+    static constexpr GatherShape kGather =
+        G == 1 ? GatherShape{2, 8, 128, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
+    static constexpr WalkShape kWalk = G == 1 ? WalkShape{1, 2, 8, 0} : WalkShape{1, 2, 2, 2};
+    template <int U> struct Raw { Tile<U> r[G]; };         // packed 16-bit pairs, as loaded
     const uint16_t *xin;
     uint16_t *xout;
     int64_t ld;
+    float inv_g;
 
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
     {
-        tile_load16<U, FULL, NT>(xin + static_cast<int64_t>(row) * ld + off, mask, raw.x);
+        const uint16_t *p = xin + static_cast<int64_t>(row) * G * ld + off;
+#pragma unroll
+        for (int j = 0; j < G; ++j) tile_load16<U, FULL, NT>(p + j * ld, mask, raw.r[j]);
     }
-    template <int U, bool FULL, bool NT, bool COMMIT = true>
-    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
+    template <int U>
+    static __device__ __forceinline__ void widen(const Tile<U> &packed, Work<U> &t)
     {
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const u4 w = __builtin_bit_cast(u4, raw.x.v[u]);
+            const u4 w = __builtin_bit_cast(u4, packed.v[u]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const unsigned h = (w[e >> 1] >> (16 * (e & 1))) & 0xffffu;
                 t.v[2 * u + (e >> 2)][e & 3] = IEEE_HALF ? f16_bits_to_float(h) : bf16_bits_to_float(h);
             }
         }
+    }
+    template <int U, bool FULL, bool NT, bool COMMIT = true>
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
+    {
+        if constexpr (G == 1) {
+            widen<U>(raw.r[0], t);
+        } else {
+            t = widened_tree_sum<G, U>(raw.r);
+#pragma unroll
+            for (int u = 0; u < 2 * U; ++u) t.v[u] = t.v[u] * inv_g;
+        }
+    }
+    // tree_sum's order (split at the largest power of two below N) with the leaves widened on
+    // demand, so only one partial sum per tree level is alive at a time.
+    template <int N, int U>
+    static __device__ __forceinline__ Work<U> widened_tree_sum(const Tile<U> *r)
+    {
+        Work<U> s;
+        if constexpr (N == 1) {
+            widen<U>(r[0], s);
+        } else {
+            constexpr int H = (N > 16) ? 16 : (N > 8) ? 8 : (N > 4) ? 4 : (N > 2) ? 2 : 1;
+            const Work<U> a = widened_tree_sum<H, U>(r);
+            const Work<U> b = widened_tree_sum<N - H, U>(r + H);
+#pragma unroll
+            for (int u = 0; u < 2 * U; ++u) s.v[u] = a.v[u] + b.v[u];
+        }
+        return s;
     }
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
@@ -404,7 +439,9 @@ struct Row16Op {
             }
             packed.v[u] = __builtin_bit_cast(f4, w);
         }
-        tile_store16<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
+        uint16_t *p = xout + static_cast<int64_t>(row) * G * ld + off;
+#pragma unroll
+        for (int j = 0; j < G; ++j) tile_store16<U, FULL, NT>(p + j * ld, mask, packed);
     }
 };
 
@@ -750,7 +787,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     typename Op::template Raw<U> mine;
     auto mix_and_store = [&](auto full_c, const unsigned (&m)[U], int peer) {
         constexpr bool FULL = decltype(full_c)::value;
-        constexpr bool kOneAtATime = Op::kRawPerSlice * U >= 16;
+        constexpr bool kOneAtATime = Op::kRawPerSlice * Op::template Work<U>::kN >= 16;   // fp32 tiles per phase
         typename Op::template Work<U> a, out;
         if (skip_mix) {
             op.template finish<U, FULL, NT, true>(row, off, m, mine, a);

@@ -28,7 +28,8 @@ TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE, TUNE_ORDERED, TUNE
 
 EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_segments",
            "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",
-           "cx_sgd_fused_mix", "cx_hier_sgd_fused_mix", "cx_gossip_mix_bf16", "cx_gossip_mix_f16", "cx_copy_baseline", "cx_set_tuning",
+           "cx_sgd_fused_mix", "cx_hier_sgd_fused_mix", "cx_gossip_mix_bf16", "cx_gossip_mix_f16", "cx_hier_mix_bf16", "cx_hier_mix_f16",
+           "cx_copy_baseline", "cx_set_tuning",
            "cx_get_tuning"]
 
 
@@ -62,6 +63,8 @@ def lib() -> ctypes.CDLL:
     L.cx_gossip_mix.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
     L.cx_gossip_mix_bf16.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
     L.cx_gossip_mix_f16.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
+    L.cx_hier_mix_bf16.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, u32, vp]
+    L.cx_hier_mix_f16.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, u32, vp]
     L.cx_hier_mix.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, u32, vp]
     L.cx_pushsum_mix.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, u32, vp]
     L.cx_sgd_fused_mix.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32,
@@ -166,6 +169,26 @@ def cx_gossip_mix_bf16(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int =
 def cx_gossip_mix_f16(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int = 0, stream=None):
     """x: torch.float16 (or int16 bit patterns) [W][ld]."""
     _mix16("cx_gossip_mix_f16", x_in, x_out, P, seg_off_dev, peers_dev, flags, stream)
+
+
+def _hier16(name, x_in, x_out, P, G, seg_off_dev, leader_peers_dev, flags, stream):
+    W, ld = _shape(x_in)
+    if x_in.element_size() != 2 or x_out.element_size() != 2:
+        raise ValueError("expected 16-bit elements")
+    S = seg_off_dev.numel() - 1
+    _ok(name, getattr(lib(), name)(_dptr(x_in), _dptr(x_out), ld, W, P, G, S, _dptr(seg_off_dev),
+                                   _dptr(leader_peers_dev) if leader_peers_dev is not None else None,
+                                   flags, _stream(stream)))
+
+
+def cx_hier_mix_bf16(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flags: int = 0, stream=None):
+    """x: torch.bfloat16 (or int16 bit patterns) [W][ld]."""
+    _hier16("cx_hier_mix_bf16", x_in, x_out, P, G, seg_off_dev, leader_peers_dev, flags, stream)
+
+
+def cx_hier_mix_f16(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flags: int = 0, stream=None):
+    """x: torch.float16 (or int16 bit patterns) [W][ld]."""
+    _hier16("cx_hier_mix_f16", x_in, x_out, P, G, seg_off_dev, leader_peers_dev, flags, stream)
 
 
 def cx_hier_mix(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flags: int = 0,

@@ -120,6 +120,30 @@ def test_c2_16bit_rows_sampled_all_rounds(fmt):
     free(a, b, c, xd)
 
 
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_c3_16bit_hierarchical_sampled_all_rounds(fmt):
+    wl = WL.WORKLOADS["C3"]
+    so = WL.seg_off_for(wl)
+    ld = padded(wl.P)
+    tabs = cx.cx_topology_gen(wl.seed, wl.L, wl.S, 0, wl.rounds)
+    mix, dt = {"bf16": (cx.cx_hier_mix_bf16, torch.bfloat16), "f16": (cx.cx_hier_mix_f16, torch.float16)}[fmt]
+    xd = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld).to(dt)
+    cols, sso, cold = sample(wl, so)
+    grab = lambda t: host(t.view(torch.int16).index_select(1, cold)).view(np.uint16)
+    sub = grab(xd)
+    a, b, c = xd, torch.empty_like(xd), xd.clone()
+    sod = dev(so)
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        mix(a, b, wl.P, wl.G, sod, t)
+        a, b = b, a
+        mix(c, c, wl.P, wl.G, sod, t)
+        sub = O.hier_mix16_f32(fmt, sub, len(cols), wl.G, sso, tabs[r])
+    torch.cuda.synchronize()
+    assert (grab(a) == sub).all() and (grab(c) == sub).all()
+    free(a, b, c, xd)
+
+
 def hier_bound(xsub, G, ysub64, pe, sso):
     W, n = xsub.shape
     L = W // G

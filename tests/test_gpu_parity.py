@@ -378,6 +378,58 @@ def test_16bit_every_pattern_against_three_partners(fmt):
     assert same(host(out).view(np.uint16), want) and same(host(xd).view(np.uint16), want)
 
 
+# ------------------------------------------------------------- 16-bit hierarchical rows
+def _fmt16(fmt):
+    return ((cx.cx_hier_mix_bf16, O.f32_to_bf16, same_bf16) if fmt == "bf16" else
+            (cx.cx_hier_mix_f16, O.f32_to_f16, same_f16))
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+@pytest.mark.parametrize("W,G,P,ld,S", [(2, 2, 5, 8, 1), (4, 2, 13, 16, 2), (8, 1, 3001, 3008, 3), (8, 4, 9001, 9008, 4),
+                                        (16, 8, 8195, 8320, 7), (24, 8, 5003, 5008, 5), (64, 8, 3000, 3000, 5),
+                                        (32, 4, 4100, 4104, 3), (8, 8, 2500, 2504, 2)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_hier16_bit_exact(fmt, W, G, P, ld, S, inplace):
+    mix, narrow, same = _fmt16(fmt)
+    x = narrow(WL.gen_matrix(W, P, 1.0, seed=W * 11 + P, ld=ld))
+    so = WL.equal_seg_off(P, S)
+    L = W // G
+    pe = O.topology(75, L, S, 0, 1)[0] if L > 1 else None
+    want = O.hier_mix16_f32(fmt, x, P, G, so, pe)
+    xd = dev(x.view(np.int16))
+    out = xd if inplace else xd.clone()
+    mix(xd, out, P, G, dev(so), dev(pe) if pe is not None else None)
+    torch.cuda.synchronize()
+    assert same(host(out).view(np.uint16), want)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+@pytest.mark.parametrize("tuning", ALL_TUNINGS)
+def test_hier16_rounds_under_every_launch_shape(fmt, tuning):
+    mix, narrow, same = _fmt16(fmt)
+    W, G, P, ld, S, R = 32, 8, 6007, 6016, 5, 3
+    rng = np.random.default_rng(76)
+    x = narrow(WL.gen_matrix(W, ld, 1.0, seed=76))
+    if fmt == "f16":                 # a share of arbitrary bit patterns: subnormals, large values, NaN, infinity
+        raw = rng.integers(0, 65536, size=x.shape).astype(np.uint16)
+        x = np.where(rng.random(x.shape) < 0.1, raw, x)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(76, W // G, S, 0, R)
+    want = x
+    with np.errstate(all="ignore"):
+        for r in range(R):
+            want = O.hier_mix16_f32(fmt, want, P, G, so, tabs[r])
+    with Tuning(*tuning):
+        a = dev(x.view(np.int16))
+        y0, y1 = dev(x.view(np.int16)), dev(x.view(np.int16))
+        for r in range(R):
+            mix(a, a, P, G, dev(so), dev(tabs[r]))
+            mix(y0, y1, P, G, dev(so), dev(tabs[r]))
+            y0, y1 = y1, y0
+        torch.cuda.synchronize()
+    assert same(host(a).view(np.uint16), want) and same(host(y0).view(np.uint16), want)
+
+
 # ------------------------------------------------------------------------ hierarchical
 def hier_tol(x, G, P, y64, pe, so):
     """1e-6 relative to max(|ref|, mean |x| over the rows that enter the result)."""

@@ -152,6 +152,16 @@ def test_mix_calls_reject_bad_arguments_on_the_host():
         assert bf16(fn, ld=60, P=60) == -5                  # 16-bit rows need ld % 8 == 0
         assert bf16(fn, x_out=A + 32) == -6 and bf16(fn, flags=4) == -8
 
+    for fn in (L.cx_hier_mix_bf16, L.cx_hier_mix_f16):
+        def hier16(**kw):
+            a = {**ok, "G": 2, **kw}
+            return fn(a["x_in"], a["x_out"], a["ld"], a["W"], a["P"], a["G"], a["S"], a["so"], a["pe"],
+                      a["flags"], a["st"])
+        assert hier16(x_in=None) == -1 and hier16(so=None) == -1 and hier16(pe=None) == -1
+        assert hier16(G=3) == -2 and hier16(G=0) == -2 and hier16(ld=56) == -2
+        assert hier16(ld=60, P=60) == -5 and hier16(x_out=A + 32) == -6 and hier16(flags=4) == -8
+        assert hier16(G=16, W=32) == -8
+
     assert L.cx_copy_baseline(None, B, 64, None) == -1
     assert L.cx_copy_baseline(A, B, 6, None) == -2
     assert L.cx_copy_baseline(A, A + 64, 64, None) == -6
