@@ -297,16 +297,18 @@ def main():
 
     if args.all:
         others = {}
-        plan = [("C1", "gossip", 50), ("C3", "hier", 20), ("C3", "hiersgd", 20), ("C4", "fused", 10),
-                ("C4", "pushsum", 20), ("C5", "hier", 10)]
-        for name, k, steps in plan:
-            if name == args.workload and k == kind:
+        plan = [("C1", "gossip", None, 50), ("C2", "gossip", "bf16", 50), ("C2", "gossip", "f16", 50),
+                ("C3", "hier", None, 20), ("C3", "hier", "bf16", 20), ("C3", "hiersgd", None, 20),
+                ("C4", "fused", None, 10), ("C4", "pushsum", None, 20), ("C5", "hier", None, 10)]
+        for name, k, r16, steps in plan:
+            if name == args.workload and k == kind and r16 == rows16:
                 continue
-            r = Runner(WL.WORKLOADS[name], k, steps + 3, in_place=args.in_place)
+            r = Runner(WL.WORKLOADS[name], k, steps + 3, in_place=args.in_place, rows16=r16)
             rr = r.run(steps, 3)
-            rr["workload"] = describe(WL.WORKLOADS[name])
+            rr["workload"] = describe(WL.WORKLOADS[name], r16 or "fp32")
             rr["frac_of_hbm_peak_kernel"] = rr["kernel_GBps"] / HBM_PEAK_GBPS
-            others[f"{name}:{k}"] = rr
+            rr["traffic"] = measured_traffic(name, k, args.in_place, r16)
+            others[f"{name}:{k}" + (f":{r16}" if r16 else "")] = rr
             del r
             torch.cuda.empty_cache()
         out["other_workloads"] = others
