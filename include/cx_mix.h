@@ -230,8 +230,8 @@ int cx_gossip_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t
  * [W][ld] of bfloat16 / binary16 bit patterns, ld % 8 == 0.  Every value is widened exactly,
  * the group sum (fixed pairwise tree), the scaling by 1/G and the leader average run in fp32 as
  * in cx_hier_mix, and the result is rounded ONCE (nearest even) before it is written to the G
- * rows of the group.  G = 1, 2, 4, 8 (CX_ERR_UNSUPPORTED otherwise); G = 1 equals
- * cx_gossip_mix_bf16 / _f16.  Everything else as cx_hier_mix.
+ * rows of the group.  G = 1, 2, 4, 8 (CX_ERR_UNSUPPORTED otherwise); G = 1 is
+ * cx_gossip_mix_bf16 / _f16 (and needs W >= 2).  Everything else as cx_hier_mix.
  */
 int cx_hier_mix_bf16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int64_t P,
                      int32_t G, int32_t S, const int64_t *seg_off_dev,

@@ -10,6 +10,10 @@ int hier_mix16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int
 {
     if (!seg_off_dev || !x_in || !x_out) return CX_ERR_NULL;
     if (W < 1 || G < 1 || W % G != 0) return CX_ERR_SHAPE;
+    if (G == 1 && W >= 2)             // groups of one: the flat 16-bit mix, bit for bit
+        return IEEE_HALF ? cx_gossip_mix_f16(x_in, x_out, ld, W, P, S, seg_off_dev, leader_peers_dev, flags, stream)
+                         : cx_gossip_mix_bf16(x_in, x_out, ld, W, P, S, seg_off_dev, leader_peers_dev, flags, stream);
+    if (G == 1) return CX_ERR_SHAPE;  // a single row has nothing to mix with
     const int32_t L = W / G;
     if (L > CX_MAX_ROWS) return CX_ERR_SHAPE;
     if (L > 1 && !leader_peers_dev) return CX_ERR_NULL;
@@ -21,7 +25,6 @@ int hier_mix16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int
     const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
     const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
     switch (G) {
-    case 1: return launch_mix<Row16Op<IEEE_HALF, 1>>(Row16Op<IEEE_HALF, 1>{x_in, x_out, ld, inv_g}, a);
     case 2: return launch_mix<Row16Op<IEEE_HALF, 2>>(Row16Op<IEEE_HALF, 2>{x_in, x_out, ld, inv_g}, a);
     case 4: return launch_mix<Row16Op<IEEE_HALF, 4>>(Row16Op<IEEE_HALF, 4>{x_in, x_out, ld, inv_g}, a);
     case 8: return launch_mix<Row16Op<IEEE_HALF, 8>>(Row16Op<IEEE_HALF, 8>{x_in, x_out, ld, inv_g}, a);

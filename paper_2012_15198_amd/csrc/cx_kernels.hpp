@@ -364,6 +364,7 @@ struct Row16Op {
     static constexpr GatherShape kGather =
         G == 1 ? GatherShape{2, 8, 128, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
     static constexpr WalkShape kWalk = G == 1 ? WalkShape{1, 2, 8, 0} : WalkShape{1, 2, 2, 2};
+    static constexpr int kMaxU = G == 1 ? 4 : 1;           // grouped: one slice per lane fills the registers
     template <int U> struct Raw { Tile<U> r[G]; };         // packed 16-bit pairs, as loaded
     const uint16_t *xin;
     uint16_t *xout;
@@ -953,10 +954,20 @@ struct MixArgs {
 
 // A (slices, depth) pair is built for an operator only if its ring of in-flight rows stays
 // within the register file without spilling (at least two waves per SIMD stay resident).
+template <class Op, class = void>
+struct MaxSlices {
+    static constexpr int value = 4;
+};
+template <class Op>
+struct MaxSlices<Op, std::void_t<decltype(Op::kMaxU)>> {
+    static constexpr int value = Op::kMaxU;                // an operator may build fewer shapes
+};
+
 template <class Op, int U, int D>
 constexpr bool fits()
 {
-    return Op::kRawPerSlice * U * D * 4 <= 128 && !(U == 4 && Op::kRawPerSlice * D >= 8);
+    return U <= MaxSlices<Op>::value && Op::kRawPerSlice * U * D * 4 <= 128 &&
+           !(U == 4 && Op::kRawPerSlice * D >= 8);
 }
 
 template <class Op, int U, int D>
@@ -1004,6 +1015,9 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
                 int *status)
 {
     if (want_u != U) return false;
+    if constexpr (U > MaxSlices<Op>::value) {
+        return false;
+    } else {
     const int64_t chunk_cols = static_cast<int64_t>(kWave) * Op::kElems * U * waves;
     const int64_t nchunks = (a.P + chunk_cols - 1) / chunk_cols;
     const int nxcd = xcd_aware ? 8 : 1;
@@ -1058,6 +1072,7 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
                            static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, slot);
     *status = hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
     return true;
+    }
 }
 
 template <class Op>
@@ -1070,7 +1085,7 @@ int launch_mix(const Op &op, const MixArgs &a)
         int u = cx_get_tuning(0);
         if (u != 1 && u != 2 && u != 4) u = Op::kGather.U;
         while (u > 1 && Op::kRawPerSlice * u > 8) u >>= 1;   // the rows in flight must fit the registers
-        if (Op::kRawPerSlice >= 8) u = 1;
+        if (Op::kRawPerSlice >= 8 || u > MaxSlices<Op>::value) u = 1;
         int waves = cx_get_tuning(1);
         if (waves < 1 || waves > kMaxWavesPerBlock) waves = Op::kGather.waves;
         const int nt = cx_get_tuning(2) == 0 ? 0 : 1;
