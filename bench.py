@@ -5,7 +5,11 @@ A step is one gossip round over the whole workload: generate the round's peer ta
 (Algorithm 2, host), upload them (a few KB), and run one mixing launch over all W rows
 (Algorithm 1) from one HBM-resident buffer into the other (ping-pong; --in-place updates a
 single buffer instead).  The parameter matrix is resident in HBM before timing starts.
-Prints ONE JSON line (see the design doc for the fields).
+Prints ONE JSON line: the whole-step rate (`value`, algorithmic GB/s = 8 B per worker-parameter
+and round; 20 B with the fused optimizer), `roofline` (the mixing kernel's own rate from events
+around each launch, against the 8 TB/s HBM peak, with the profiled HBM traffic), `copy_ceiling`
+(a plain copy of the same footprint), `topology_gen` (host time of the table generator) and
+`cpu_baseline` (the CPU oracle timed on this host).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--all]
                     [--no-cpu-baseline]

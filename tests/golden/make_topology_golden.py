@@ -1,6 +1,7 @@
 #!/usr/bin/env python3
 """Writes tests/golden/topology_seed2_n8.txt: peer tables of the frozen topology spec
-(Algorithm 2 of the paper with the readings listed in the design doc), computed by the CPU oracle
+(Algorithm 2 of the paper: sequential fair draw, dead-end swap, counter-based draws keyed by seed,
+round and segment), computed by the CPU oracle
 ONLY.  The library's generator is tested against this file, so a change that alters both
 sides in the same way is still caught.
 
