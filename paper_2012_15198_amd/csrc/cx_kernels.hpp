@@ -362,7 +362,7 @@ struct Row16Op {
     template <int U> using Work = Tile<2 * U>;             // 8 fp32 values per slice
     static constexpr int kRawPerSlice = G;
     static constexpr GatherShape kGather =
-        G == 1 ? GatherShape{2, 8, 128, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
+        G == 1 ? GatherShape{1, 8, 128, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
     static constexpr WalkShape kWalk = G == 1 ? WalkShape{1, 2, 8, 0} : WalkShape{1, 2, 2, 2};
     static constexpr int kMaxU = G == 1 ? 4 : 1;           // grouped: one slice per lane fills the registers
     template <int U> struct Raw { Tile<U> r[G]; };         // packed 16-bit pairs, as loaded
