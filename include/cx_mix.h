@@ -169,8 +169,13 @@ int cx_pushsum_mix(const float *x_in, float *x_out, const float *w_in, float *w_
 /* ------------------------------------------------------------------------------------
  * cx_sgd_fused_mix -- local momentum-SGD step fused in front of Algorithm 1's averaging
  * (Section 3.1: parameters are averaged after the gradient has been applied):
- *     t = g + wd * x ;  v' = mu * v + t ;  h = x - lr * v'       (per row, fp32, no FMA)
- *     x_out[i][c] = (h[i][c] + h[peers[s][i]][c]) * 0.5f ;  v_out = v'
+ *     t = g + wd * x ;  v' = mu * v + t ;  h = x - lr * v'                       (per row)
+ *     x_out[i][c] = fp32((h[i][c] + h[peers[s][i]][c]) * 0.5) ;  v_out = fp32(v')
+ * The whole chain, the average included, is evaluated in fp64 (inputs widened exactly, lr, mu,
+ * wd as the doubles of their fp32 values, operations in the order written, no fused
+ * multiply-add); v' and x_out are each rounded ONCE to fp32 (nearest even).  Results are
+ * therefore the correctly rounded values of that fp64 formula: within 2^-24 relative of it,
+ * however large lr * v' is against x.
  * v_out may equal v_in (in place) and x_out may equal x_in; g is only read.
  * x, v and g share shape and ld.  Each of x, v, g is read once, x and v written once.
  * Errors: as cx_gossip_mix.
@@ -185,16 +190,17 @@ int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *
  * (1) the gradients of the G workers of a group are reduced at the group's leader, which
  * applies them to its model; (2) the L = W / G leaders gossip segment-wise (Algorithm 1);
  * (3) each leader's result is broadcast to its group.
- *     gbar_q = (pairwise-tree fp32 sum of the group's G gradient rows) * (1.0f / G)
+ *     gbar_q = (g_{qG} + g_{qG+1} + ... + g_{qG+G-1}) / G              (summed in row order)
  *     t = gbar_q + wd * x_q ;  v'_q = mu * v_q + t ;  h_q = x_q - lr * v'_q     (x_q = leader row)
- *     y_q = (h_q + h_{leader_peers[s][q]}) * 0.5f                        (skipped when L == 1)
- *     every row of group q  <-  y_q ;  v_out[q] = v'_q
+ *     y_q = (h_q + h_{leader_peers[s][q]}) * 0.5                         (skipped when L == 1)
+ *     every row of group q  <-  fp32(y_q) ;  v_out[q] = fp32(v'_q)
+ * evaluated in fp64 and rounded once, as in cx_sgd_fused_mix.
  *   x_in, x_out, g   float32 [W][ld]; of x_in only the leader rows (q * G) are read
  *   v_in, v_out      float32 [L][ld]: the leaders' momentum
  * x_out may equal x_in and v_out may equal v_in (then both must); with L == 1 this is
  * AllReduce-SGD.  Per worker-parameter it moves 8 + 12/G bytes (read g, write x; the leader
  * also reads x, v and writes v).
- * Errors: as cx_hier_mix (group sizes 1, 2, 4, 8); CX_ERR_ALIAS also if exactly one of x, v is
+ * Errors: as cx_hier_mix (group sizes 1, 2, 4, 8, 16); CX_ERR_ALIAS also if exactly one of x, v is
  * updated in place, or v overlaps x or g.
  */
 int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *v_out,

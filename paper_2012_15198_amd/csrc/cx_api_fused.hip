@@ -20,7 +20,7 @@ int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *
         any_overlap(x_out, v_in, bytes) || any_overlap(x_out, v_out, bytes) ||
         any_overlap(g, x_out, bytes) || any_overlap(g, v_out, bytes))
         return CX_ERR_ALIAS;
-    const FusedOp op{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd};
+    const FusedOp op{x_in, x_out, v_in, v_out, g, ld, SgdStep{lr, mu, wd}};
     const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream),
                     x_in != x_out && v_in != v_out, 1};
     return launch_mix<FusedOp>(op, a);

@@ -30,15 +30,16 @@ int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, fl
         overlap2(g, xbytes, v_out, vbytes) || any_overlap(g, x_out, xbytes))
         return CX_ERR_ALIAS;
     const hipStream_t st = static_cast<hipStream_t>(stream);
-    const float inv_g = 1.0f / static_cast<float>(G);
+    const SgdStep sgd{lr, mu, wd};
     const int skip = (L == 1) ? 1 : 0;
     const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
     const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
     switch (G) {
-    case 1: return launch_mix<HierFusedOp<1>>(HierFusedOp<1>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 2: return launch_mix<HierFusedOp<2>>(HierFusedOp<2>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 4: return launch_mix<HierFusedOp<4>>(HierFusedOp<4>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
-    case 8: return launch_mix<HierFusedOp<8>>(HierFusedOp<8>{x_in, x_out, v_in, v_out, g, ld, lr, mu, wd, inv_g}, a);
+    case 1: return launch_mix<HierFusedOp<1>>(HierFusedOp<1>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 2: return launch_mix<HierFusedOp<2>>(HierFusedOp<2>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 4: return launch_mix<HierFusedOp<4>>(HierFusedOp<4>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 8: return launch_mix<HierFusedOp<8>>(HierFusedOp<8>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 16: return launch_mix<HierFusedOp<16>>(HierFusedOp<16>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     default: return CX_ERR_UNSUPPORTED;
     }
 }

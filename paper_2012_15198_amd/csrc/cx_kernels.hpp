@@ -55,6 +55,10 @@
 #include <mutex>
 #include <type_traits>
 
+#define CX_SCHED_FN __device__ __forceinline__
+#include "cx_schedule.hpp"          // build_schedule: the cycle order of a peer table
+static_assert(CX_MAX_ROWS <= (1 << kRowBits), "row ids must fit the schedule's packed fields");
+
 #pragma clang fp contract(off)
 
 extern "C" int cx_get_tuning(int32_t key);
@@ -64,15 +68,29 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
-constexpr int kLastBit = 1 << 30;          // schedule entry flag: last row of its cycle
-constexpr int kRowMask = kLastBit - 1;
 constexpr int kMaxWavesPerBlock = 8;
+
+typedef double d4 __attribute__((ext_vector_type(4)));
 
 template <int U>
 struct Tile {
     static constexpr int kN = U;
+    static constexpr int kRegs = 4;        // 32-bit registers per vector
     f4 v[U];
 };
+
+// The same columns held as doubles: the optimizer operators carry their whole chain,
+// pairwise average included, in fp64 registers and round once on the way out.
+template <int U>
+struct WideTile {
+    static constexpr int kN = U;
+    static constexpr int kRegs = 8;
+    d4 v[U];
+};
+
+// Algorithm 1's averaging line on one vector of columns, in the precision of the tile.
+__device__ __forceinline__ f4 average(const f4 &a, const f4 &b) { return (a + b) * 0.5f; }
+__device__ __forceinline__ d4 average(const d4 &a, const d4 &b) { return (a + b) * 0.5; }
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -208,13 +226,35 @@ struct MeanOp {
     }
 };
 
-// Momentum-SGD applied as the row arrives; the walk then mixes the updated rows.
+// Momentum-SGD applied as the row arrives; the mix then averages the updated rows.
+// The whole chain runs in fp64 registers, in the order the formula is written:
+//     t = g + wd*x ;  v' = mu*v + t ;  h = x - lr*v' ;  x' = (h_i + h_peer) * 0.5
+// (every input widened exactly, the hyper-parameters as the doubles of their fp32 values, no
+// fused multiply-add), and v' and x' are each rounded ONCE to fp32 when they are stored.  An
+// fp32 chain would round six times against intermediates larger than the result and misses a
+// 1e-6 relative bound once the momentum has grown; the kernel is bound by HBM bandwidth, so
+// the fp64 rate is not what limits it.
+__device__ __forceinline__ d4 widen(const f4 &a) { return __builtin_convertvector(a, d4); }
+__device__ __forceinline__ f4 narrow(const d4 &a) { return __builtin_convertvector(a, f4); }
+
+struct SgdStep {
+    double lr, mu, wd;
+    // one optimizer step on a vector of columns: returns h, leaves v' in `v`
+    __device__ __forceinline__ d4 apply(const d4 &x, d4 &v, const d4 &g) const
+    {
+        const d4 decayed = g + x * wd;
+        v = v * mu + decayed;
+        return x - v * lr;
+    }
+};
+
 struct FusedOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
-    template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
+    template <int U> using Work = WideTile<U>;             // the updated row, in fp64
     static constexpr int kRawPerSlice = 3;
     static constexpr GatherShape kGather{1, 8, 256, 3};
-    static constexpr WalkShape kWalk{4, 2, 4, 2};
+    static constexpr WalkShape kWalk{2, 2, 4, 2};
+    static constexpr int kMaxU = 2;                        // fp64 rows: two slices per lane fill the registers
     template <int U> struct Raw { Tile<U> x, v, g; };
     const float *xin;
     float *xout;
@@ -222,7 +262,7 @@ struct FusedOp {
     float *vout;
     const float *g;
     int64_t ld;
-    float lr, mu, wd;
+    SgdStep sgd;
 
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
@@ -234,36 +274,41 @@ struct FusedOp {
     }
     // COMMIT: also write v' of this row (false when the row is only recomputed as a partner)
     template <int U, bool FULL, bool NT, bool COMMIT = true>
-    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Tile<U> &t) const
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
     {
-        Tile<U> v;
+        Tile<U> v32;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const f4 decayed = raw.g.v[u] + raw.x.v[u] * wd;   // g' = g + wd*x
-            v.v[u] = raw.v.v[u] * mu + decayed;                // v' = mu*v + g'
-            t.v[u] = raw.x.v[u] - v.v[u] * lr;                 // x_half = x - lr*v'
+            d4 v = widen(raw.v.v[u]);
+            t.v[u] = sgd.apply(widen(raw.x.v[u]), v, widen(raw.g.v[u]));
+            v32.v[u] = narrow(v);
         }
-        if constexpr (COMMIT) tile_store<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v);
+        if constexpr (COMMIT) tile_store<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
     }
     template <int U, bool FULL, bool NT>
-    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Tile<U> &t) const
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
     {
-        tile_store<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, t);
+        Tile<U> out;
+#pragma unroll
+        for (int u = 0; u < U; ++u) out.v[u] = narrow(t.v[u]);
+        tile_store<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, out);
     }
 };
 
 // Hierarchical step with gradients: a gossiping row is a group; loading it reduces the G
-// gradient rows (pairwise tree), applies the momentum-SGD step to the LEADER's parameters
-// and momentum, and hands the updated leader parameters to the walk; storing broadcasts.
+// gradient rows, applies the momentum-SGD step to the LEADER's parameters and momentum, and
+// hands the updated leader parameters to the mix; storing broadcasts.  fp64 registers as in
+// FusedOp: the gradients are summed in row order starting from zero and divided by G.
 template <int G>
 struct HierFusedOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
-    template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
+    template <int U> using Work = WideTile<U>;             // the updated leader row, in fp64
     static constexpr int kRawPerSlice = G + 2;
     // out-of-place launch: slices, waves, group visit KB per XCD
     static constexpr GatherShape kGather =
         G == 1 ? GatherShape{1, 8, 256, 0} : G <= 4 ? GatherShape{1, 8, 512, 0} : GatherShape{1, 8, 1024, 0};
     static constexpr WalkShape kWalk = G <= 4 ? WalkShape{1, 4, 2, 2} : WalkShape{1, 2, 2, 2};
+    static constexpr int kMaxU = G <= 2 ? 2 : 1;
     template <int U> struct Raw { Tile<U> g[G], x, v; };
     const float *xin;
     float *xout;
@@ -271,7 +316,7 @@ struct HierFusedOp {
     float *vout;          // [L][ld]
     const float *g;       // [W][ld]
     int64_t ld;
-    float lr, mu, wd, inv_g;
+    SgdStep sgd;
 
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
@@ -283,25 +328,30 @@ struct HierFusedOp {
         tile_load<U, FULL, NT>(vin + static_cast<int64_t>(row) * ld + off, mask, raw.v);
     }
     template <int U, bool FULL, bool NT, bool COMMIT = true>
-    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Tile<U> &t) const
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
     {
-        const Tile<U> gsum = tree_sum<G, U>(raw.g);
-        Tile<U> v;
+        Tile<U> v32;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const f4 gbar = gsum.v[u] * inv_g;
-            const f4 decayed = gbar + raw.x.v[u] * wd;
-            v.v[u] = raw.v.v[u] * mu + decayed;
-            t.v[u] = raw.x.v[u] - v.v[u] * lr;
+            d4 gsum = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int j = 0; j < G; ++j) gsum = gsum + widen(raw.g[j].v[u]);
+            const d4 gbar = gsum / static_cast<double>(G);
+            d4 v = widen(raw.v.v[u]);
+            t.v[u] = sgd.apply(widen(raw.x.v[u]), v, gbar);
+            v32.v[u] = narrow(v);
         }
-        if constexpr (COMMIT) tile_store<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v);
+        if constexpr (COMMIT) tile_store<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
     }
     template <int U, bool FULL, bool NT>
-    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Tile<U> &t) const
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
     {
+        Tile<U> out;
+#pragma unroll
+        for (int u = 0; u < U; ++u) out.v[u] = narrow(t.v[u]);
         float *p = xout + static_cast<int64_t>(row) * G * ld + off;
 #pragma unroll
-        for (int j = 0; j < G; ++j) tile_store<U, FULL, NT>(p + j * ld, mask, t);
+        for (int j = 0; j < G; ++j) tile_store<U, FULL, NT>(p + j * ld, mask, out);
     }
 };
 
@@ -490,50 +540,15 @@ struct PushOp {
     }
 };
 
-// ---------------------------------------------------------------------------------
-// Cycle schedule of one segment, built by one wavefront in its private LDS region.
-//   tab[0..n)  : the table, then scratch for the walk
-//   sched[0..n): rows in cycle order; kLastBit marks the last row of a cycle
-// Source of the table: shift > 0 -> row i receives from (i - shift) mod n;
-// peers == null -> identity; else peers[seg*n + i].
-// ---------------------------------------------------------------------------------
-__device__ __forceinline__ void build_schedule(int *tab, int *sched, int n, int lane,
-                                               const int32_t *peers, int seg, int shift)
-{
-    bool ok = true;
-    for (int i = lane; i < n; i += kWave) {
-        int v = i;
-        if (shift > 0) v = i >= shift ? i - shift : i - shift + n;
-        else if (peers) v = peers[static_cast<int64_t>(seg) * n + i];
-        if (static_cast<unsigned>(v) >= static_cast<unsigned>(n)) { ok = false; v = i; }
-        tab[i] = v;
-        sched[i] = 0;
-    }
-    wave_sync();
-    for (int i = lane; i < n; i += kWave) atomicAdd(&sched[tab[i]], 1);   // in-degree
-    wave_sync();
-    for (int i = lane; i < n; i += kWave) ok = ok && (sched[i] == 1);
-    const bool valid = __builtin_amdgcn_ballot_w64(!ok) == 0;
-    wave_sync();
-    if (!valid)
-        for (int i = lane; i < n; i += kWave) tab[i] = i;
-    wave_sync();
-    if (lane == 0) {
-        int k = 0;
-        for (int start = 0; start < n && k < n; ++start) {
-            if (tab[start] < 0) continue;             // already on an earlier cycle
-            int cur = start;
-            do {
-                const int nxt = tab[cur];
-                tab[cur] = ~nxt;                      // mark visited
-                sched[k++] = cur;
-                cur = nxt;
-            } while (cur != start && k < n);
-            sched[k - 1] |= kLastBit;
-        }
-    }
-    wave_sync();
-}
+// The two groups that build schedules: one wavefront in its private LDS region, or a workgroup.
+struct WaveSync {
+    __device__ __forceinline__ void sync() const { wave_sync(); }
+    __device__ __forceinline__ void add(int *p, int v) const { atomicAdd(p, v); }
+};
+struct BlockSync {
+    __device__ __forceinline__ void sync() const { __syncthreads(); }
+    __device__ __forceinline__ void add(int *p, int v) const { atomicAdd(p, v); }
+};
 
 // One lane's walk over all cycles of the schedule, software-pipelined: the global loads of
 // the rows of steps k+2 .. k+1+D are in flight while step k is averaged and stored.  Rows
@@ -578,10 +593,7 @@ __device__ __forceinline__ void walk(const Op &op, const int *sched, int n, bool
                 const bool last = (e & kLastBit) != 0;      // row k closes its cycle
                 WorkT out;
 #pragma unroll
-                for (int u = 0; u < WorkT::kN; ++u) {
-                    const f4 partner = last ? first.v[u] : nx.v[u];
-                    out.v[u] = (cur.v[u] + partner) * 0.5f;
-                }
+                for (int u = 0; u < WorkT::kN; ++u) out.v[u] = average(cur.v[u], last ? first.v[u] : nx.v[u]);
                 op.template store<U, FULL, NT>(e & kRowMask, off, mask, out);
                 if (last) first = nx;                       // step k+1 opens the next cycle
                 cur = nx;
@@ -618,9 +630,8 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
         const int64_t b = (s == 0) ? 0 : seg_off[s];
         const int64_t e = (s == S - 1) ? P : seg_off[s + 1];
         if (g1 <= P && b <= g0 && e >= g1) {
-            int *tab = lds;
-            int *sched = lds + n;
-            if (wave == 0) build_schedule(tab, sched, n, lane, peers, s, shift);
+            const int *sched = lds + n;
+            if (wave == 0) build_schedule(lds, n, lane, kWave, peers, s, shift, WaveSync{});
             __syncthreads();
             unsigned mask[U];
 #pragma unroll
@@ -630,8 +641,8 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
         }
     }
     if (tile >= ntiles) return;                 // from here on waves are independent: no block barrier
-    int *tab = lds + wave * 2 * n;
-    int *sched = tab + n;
+    int *work = lds + wave * kScheduleWords(n);
+    const int *sched = work + n;
 
     const int64_t c0 = tile * kTileCols;
     const int64_t c1 = (c0 + kTileCols < P) ? c0 + kTileCols : P;
@@ -652,7 +663,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
         if (b < c0) b = c0;
         if (e > c1) e = c1;
         if (b >= e) continue;
-        build_schedule(tab, sched, n, lane, peers, s, shift);
+        build_schedule(work, n, lane, kWave, peers, s, shift, WaveSync{});
         unsigned mask[U];
         if (b == c0 && e == c0 + kTileCols) {
 #pragma unroll
@@ -674,24 +685,27 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
 }
 
 // ---------------------------------------------------------------------------------
-// Row order of the out-of-place path.  Library-owned device memory (no allocation at run
-// time): kOrderSlots tables of kOrderEntries words per GPU and entry point.  A slot belongs
-// to ONE stream (first come, first served, for the life of the process): calls on a stream
-// run in stream order, so a slot is never rewritten while an earlier call still reads it.
-// Streams beyond the first kOrderSlots run without a table (natural row order: same
-// results, slower).
+// Row order of the out-of-place path: a table of 32-bit words in device memory that the
+// library owns (no allocation at run time), written by order_kernel and read by gather_kernel
+// through a pointer both receive as an argument.
 //
 // Entry (cluster, k): the k-th row the cluster's workgroups visit, that row's partner in the
 // segment of the cluster's first column, and a flag saying that this segment covers every
 // column of the cluster (so a whole tile of the cluster needs no segment lookup at all).
+//
+// The ordinary entry points keep kOrderSlots tables of kOrderEntries words per GPU and entry
+// point (g_order).  A slot serves ONE stream at a time: calls on a stream run in stream order,
+// so a table is never rewritten while an earlier call still reads it.  A stream keeps its slot
+// while it has work in flight; a slot whose stream has drained (or has been destroyed) can be
+// taken over by another stream.  Streams that find no free slot run without a table (natural
+// row order: same results, slower).
 // ---------------------------------------------------------------------------------
 constexpr int kOrderSlots = 4;
 constexpr int kOrderEntries = 1 << 18;
-constexpr int kOrderRowBits = 10;                     // CX_MAX_ROWS == 1 << kOrderRowBits
+constexpr int kOrderRowBits = kRowBits;
 constexpr unsigned kOrderRowField = (1u << kOrderRowBits) - 1u;
 constexpr unsigned kOrderOneSegment = 1u << (2 * kOrderRowBits);
-static_assert(CX_MAX_ROWS <= (1 << kOrderRowBits), "row ids must fit the order table's fields");
-__device__ unsigned g_order[kOrderSlots][kOrderEntries];
+__device__ __align__(256) unsigned g_order[kOrderSlots][kOrderEntries];
 
 // The row that gossiping row `row` averages with in segment s (Algorithm 1: receive_from):
 // the fixed shift of the push-sum schedule, or the peer table's entry; an entry outside
@@ -710,14 +724,13 @@ __device__ __forceinline__ int partner_of(const int32_t *__restrict__ peers, int
 __global__ __launch_bounds__(256) void order_kernel(int n, int64_t P, int S,
                                                     const int64_t *__restrict__ seg_off,
                                                     const int32_t *__restrict__ peers, int shift,
-                                                    int64_t cluster_cols, int nclusters, int slot)
+                                                    int64_t cluster_cols, int nclusters,
+                                                    unsigned *__restrict__ order)
 {
     extern __shared__ int lds[];
-    int *tab = lds;
-    int *sched = lds + n;
+    const int *sched = lds + n;
     const int s = blockIdx.x;
-    if (threadIdx.x < kWave) build_schedule(tab, sched, n, threadIdx.x, peers, s, shift);
-    __syncthreads();
+    build_schedule(lds, n, static_cast<int>(threadIdx.x), static_cast<int>(blockDim.x), peers, s, shift, BlockSync{});
     int64_t sb = (s == 0) ? 0 : seg_off[s];
     int64_t se = (s == S - 1) ? P : seg_off[s + 1];
     sb = sb < 0 ? 0 : (sb > P ? P : sb);
@@ -725,10 +738,13 @@ __global__ __launch_bounds__(256) void order_kernel(int n, int64_t P, int S,
     const int64_t c_lo = (sb + cluster_cols - 1) / cluster_cols;
     int64_t c_hi = (se + cluster_cols - 1) / cluster_cols;
     if (c_hi > nclusters) c_hi = nclusters;
-    unsigned *order = g_order[slot];
-    for (int64_t idx = threadIdx.x; idx < (c_hi - c_lo) * n; idx += blockDim.x) {
-        const int64_t c = c_lo + idx / n;
-        const int k = static_cast<int>(idx % n);
+    // the table as the schedule was built from it: a table that is not a permutation has become
+    // the identity there, but the gather serves it as written, so partners come from the source
+    const unsigned un = static_cast<unsigned>(n);
+    const unsigned total = static_cast<unsigned>(c_hi > c_lo ? c_hi - c_lo : 0) * un;   // fits: the table does
+    for (unsigned idx = threadIdx.x; idx < total; idx += blockDim.x) {
+        const unsigned k = idx % un;
+        const int64_t c = c_lo + idx / un;
         const int row = sched[k] & kRowMask;
         const int64_t last_col = (c + 1) * cluster_cols < P ? (c + 1) * cluster_cols : P;
         unsigned e = static_cast<unsigned>(row) |
@@ -757,7 +773,7 @@ template <class Op, int U, bool NT>
 __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     Op op, int n, int64_t P, int S, const int64_t *__restrict__ seg_off,
     const int32_t *__restrict__ peers, int shift, int skip_mix, unsigned nchunks, unsigned CL,
-    unsigned nwaves, int xcd_shift, int order_slot)
+    unsigned nwaves, int xcd_shift, const unsigned *__restrict__ order)
 {
     // grid: x = (chunk within cluster, xcd) with the xcd in the low bits, y = gossiping row,
     // z = cluster.  Blocks are dispatched x-fastest, so an XCD sees, for one cluster, row 0's
@@ -788,7 +804,9 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     typename Op::template Raw<U> mine;
     auto mix_and_store = [&](auto full_c, const unsigned (&m)[U], int peer) {
         constexpr bool FULL = decltype(full_c)::value;
-        constexpr bool kOneAtATime = Op::kRawPerSlice * Op::template Work<U>::kN >= 16;   // fp32 tiles per phase
+        using WorkT = typename Op::template Work<U>;
+        constexpr bool kOneAtATime = Op::kRawPerSlice * WorkT::kN >= 16 ||            // 16-byte registers per phase
+                                     (WorkT::kRegs == 8 && Op::kRawPerSlice * U >= 6);  // fp64 chains take more
         typename Op::template Work<U> a, out;
         if (skip_mix) {
             op.template finish<U, FULL, NT, true>(row, off, m, mine, a);
@@ -806,7 +824,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
                 op.template finish<U, FULL, NT, false>(peer, off, m, theirs, c);
             }
 #pragma unroll
-            for (int u = 0; u < Op::template Work<U>::kN; ++u) out.v[u] = (a.v[u] + c.v[u]) * 0.5f;
+            for (int u = 0; u < Op::template Work<U>::kN; ++u) out.v[u] = average(a.v[u], c.v[u]);
         }
         op.template store<U, FULL, NT>(row, off, m, out);
     };
@@ -817,8 +835,8 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     // segment covers the cluster, so a tile that does not hang over the row end starts all its
     // loads after a single scalar load.  Whatever the table holds, no access leaves the
     // matrix: rows are checked against n and the tile against P.
-    if (order_slot >= 0) {
-        const unsigned e = g_order[order_slot][cluster * static_cast<unsigned>(n) + blockIdx.y];
+    if (order) {
+        const unsigned e = order[cluster * static_cast<unsigned>(n) + blockIdx.y];
         const int r = static_cast<int>(e & kOrderRowField);
         const int q = static_cast<int>((e >> kOrderRowBits) & kOrderRowField);
         if (r < n) row = r;
@@ -939,6 +957,11 @@ struct MixArgs {
     hipStream_t stream;
     bool out_of_place;          // every output buffer is distinct from its input buffer
     int rows_per_gossip_row;    // G: matrix rows behind one gossiping row (cluster footprint)
+    // Row-order table supplied by the entry point (device address and capacity in words) instead
+    // of one of the library's per-stream slots; the call then fails with CX_ERR_SHAPE rather than
+    // run without a table when the workload's table does not fit.
+    unsigned *order_table = nullptr;
+    int64_t order_entries = 0;
 };
 
 // Dynamic LDS a workgroup reserves so that at most `wgs_per_cu` of them are resident on a CU
@@ -966,8 +989,11 @@ struct MaxSlices<Op, std::void_t<decltype(Op::kMaxU)>> {
 template <class Op, int U, int D>
 constexpr bool fits()
 {
-    return U <= MaxSlices<Op>::value && Op::kRawPerSlice * U * D * 4 <= 128 &&
-           !(U == 4 && Op::kRawPerSlice * D >= 8);
+    // registers of the ring of rows in flight plus the four working tiles of the walk: a
+    // workgroup of eight waves leaves each wave 256 registers
+    return U <= MaxSlices<Op>::value &&
+           Op::kRawPerSlice * U * D * 4 + 4 * Op::template Work<U>::kN * Op::template Work<U>::kRegs <= 224 &&
+           Op::kRawPerSlice * U * D * 4 <= 144 && !(U == 4 && Op::kRawPerSlice * D >= 8);
 }
 
 template <class Op, int U, int D>
@@ -980,10 +1006,10 @@ bool try_launch(const Op &op, const Launch &l, const MixArgs &a)
         const int64_t tile_cols = static_cast<int64_t>(kWave) * Op::kElems * U;
         const int64_t ntiles = (a.P + tile_cols - 1) / tile_cols;
         int waves = l.waves;
-        while (waves > 1 && sizeof(int) * 2 * static_cast<size_t>(a.n) * waves > 48 * 1024) --waves;
+        while (waves > 1 && sizeof(int) * kScheduleWords(a.n) * waves > 48 * 1024) --waves;
         const int64_t nblocks = (ntiles + waves - 1) / waves;
         const dim3 grid(static_cast<unsigned>(nblocks)), block(kWave * waves);
-        size_t lds = sizeof(int) * 2 * static_cast<size_t>(a.n) * waves;
+        size_t lds = sizeof(int) * kScheduleWords(a.n) * waves;
         if (lds < lds_reservation(l.wgs_per_cu)) lds = lds_reservation(l.wgs_per_cu);
         if (l.nt)
             hipLaunchKernelGGL((mix_kernel<Op, U, D, true>), grid, block, lds, a.stream, op, a.n, a.P,
@@ -995,18 +1021,66 @@ bool try_launch(const Op &op, const Launch &l, const MixArgs &a)
     }
 }
 
-// Order-table slot owned by `stream`, or -1 if all slots belong to other streams.
-int order_slot_for(hipStream_t stream)
+// Device address of this translation unit's g_order on the current device.  In host code the
+// array's name is only a handle: the address comes from hipGetSymbolAddress, once per device.
+constexpr int kMaxDevices = 64;
+unsigned *order_tables_base(int *device_out)
 {
     static std::mutex mu;
-    static hipStream_t owner[kOrderSlots];
-    static int used = 0;
+    static unsigned *base[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    *device_out = dev;
     std::lock_guard<std::mutex> lock(mu);
-    for (int i = 0; i < used; ++i)
-        if (owner[i] == stream) return i;
-    if (used == kOrderSlots) return -1;
-    owner[used] = stream;
-    return used++;
+    if (!base[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_order)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        base[dev] = static_cast<unsigned *>(p);
+    }
+    return base[dev];
+}
+
+// Serialises "order_kernel, then gather_kernel" of one call against other host threads, so
+// that two threads enqueueing on one stream cannot interleave their pairs.
+std::mutex &enqueue_mutex()
+{
+    static std::mutex mu;
+    return mu;
+}
+
+// The order table `stream` may write on the current device, or nullptr (run without one).
+// A stream keeps the slot it used last.  When every slot belongs to another stream, a slot
+// whose owner has no work in flight (or no longer exists) changes hands; a slot that was ever
+// used under stream capture stays with its stream, since the captured graph names it.
+unsigned *order_table_for(hipStream_t stream)
+{
+    static hipStream_t owner[kMaxDevices][kOrderSlots];
+    static bool used[kMaxDevices][kOrderSlots], pinned[kMaxDevices][kOrderSlots];
+    int dev = 0;
+    unsigned *base = order_tables_base(&dev);
+    if (!base) return nullptr;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    const bool capturing = hipStreamIsCapturing(stream, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
+    int slot = -1;
+    for (int i = 0; i < kOrderSlots && slot < 0; ++i)
+        if (used[dev][i] && owner[dev][i] == stream) slot = i;
+    for (int i = 0; i < kOrderSlots && slot < 0; ++i)
+        if (!used[dev][i]) slot = i;
+    for (int i = 0; i < kOrderSlots && slot < 0; ++i) {
+        if (pinned[dev][i]) continue;
+        hipStreamCaptureStatus ocs = hipStreamCaptureStatusNone;
+        const hipError_t q = hipStreamIsCapturing(owner[dev][i], &ocs);
+        if (q == hipSuccess && ocs != hipStreamCaptureStatusNone) continue;       // recording: leave it
+        const hipError_t busy = q == hipSuccess ? hipStreamQuery(owner[dev][i]) : q;
+        if (busy == hipErrorNotReady) continue;                                   // work in flight
+        if (busy != hipSuccess) (void)hipGetLastError();                          // the stream is gone
+        slot = i;
+    }
+    if (slot < 0) return nullptr;
+    owner[dev][slot] = stream;
+    used[dev][slot] = true;
+    if (capturing) pinned[dev][slot] = true;
+    return base + static_cast<int64_t>(slot) * kOrderEntries;
 }
 
 // Out-of-place launch: one workgroup per (gossiping row, chunk of waves * 64 * U slices).
@@ -1021,9 +1095,21 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     const int64_t chunk_cols = static_cast<int64_t>(kWave) * Op::kElems * U * waves;
     const int64_t nchunks = (a.P + chunk_cols - 1) / chunk_cols;
     const int nxcd = xcd_aware ? 8 : 1;
-    bool ordered = cx_get_tuning(8) != 0 && a.n > 1 && a.S <= 4096;
-    int slot = ordered ? order_slot_for(a.stream) : -1;
-    if (slot < 0) ordered = false;
+    // Rows in cycle order pay when the partner's fetch has to be kept out of HBM; a matrix that
+    // the last-level cache holds whole gains nothing from the extra launch.
+    const int64_t matrix_bytes = static_cast<int64_t>(a.n) * a.rows_per_gossip_row * a.P * (16 / Op::kElems);
+    bool ordered = cx_get_tuning(8) != 0 && a.n > 1 && a.S <= 4096 &&
+                   (a.order_table || cx_get_tuning(8) == 1 || matrix_bytes > (64LL << 20));
+    std::lock_guard<std::mutex> enqueue_lock(enqueue_mutex());
+    unsigned *order = nullptr;
+    int64_t order_entries = kOrderEntries;
+    if (ordered && a.order_table) {
+        order = a.order_table;
+        order_entries = a.order_entries;
+    } else if (ordered) {
+        order = order_table_for(a.stream);
+    }
+    if (!order) ordered = false;
     int64_t cl = cl_req;
     if (cl < 1) {
         // ordered rows: the operator's visit length per XCD (shorter visits lose DRAM row
@@ -1034,9 +1120,15 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
         if (cl < 1) cl = 1;
     }
     if (ordered) {                                // the order table must fit its slot
-        const int64_t max_clusters = kOrderEntries / a.n - nxcd;
-        const int64_t min_cl = (nchunks + max_clusters - 1) / max_clusters;
-        if (cl < min_cl) cl = min_cl;
+        const int64_t max_clusters = order_entries / a.n - nxcd;
+        if (max_clusters < 1) { if (a.order_table) { *status = CX_ERR_SHAPE; return true; } ordered = false; }
+        else {
+            const int64_t min_cl = (nchunks + max_clusters - 1) / max_clusters;
+            if (cl < min_cl) {
+                if (a.order_table) { *status = CX_ERR_SHAPE; return true; }   // beyond the stated maximum
+                cl = min_cl;
+            }
+        }
     }
     if (cl > 4096) cl = 4096;
     int64_t clusters = (nchunks + cl * nxcd - 1) / (cl * nxcd);
@@ -1047,16 +1139,20 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     if (cl * nxcd > 0x7fffffffLL || clusters > 65535 || a.n > 65535) { *status = CX_ERR_SHAPE; return true; }
     // the kernel numbers chunks and tiles, the grid's padding included, in 32 bits
     if ((clusters * nxcd * cl + 1) * waves > 0x7fffffffLL) { *status = CX_ERR_SHAPE; return true; }
-    if (clusters * nxcd * a.n > kOrderEntries) ordered = false;   // table too large: natural row order
+    if (ordered && clusters * nxcd * a.n > order_entries) {        // table too large: natural row order
+        if (a.order_table) { *status = CX_ERR_SHAPE; return true; }
+        ordered = false;
+    }
     const dim3 grid(static_cast<unsigned>(cl * nxcd), static_cast<unsigned>(a.n),
                     static_cast<unsigned>(clusters));
     const dim3 block(kWave * waves);
     const int xcd_shift = xcd_aware ? 3 : 0;
-    if (!ordered) slot = -1;
+    if (!ordered) order = nullptr;
     if (ordered) {
         const int64_t nclusters = clusters * nxcd;
-        hipLaunchKernelGGL(order_kernel, dim3(a.S), dim3(256), sizeof(int) * 2 * a.n, a.stream, a.n, a.P,
-                           a.S, a.seg_off, a.peers, a.shift, cl * chunk_cols, static_cast<int>(nclusters), slot);
+        hipLaunchKernelGGL(order_kernel, dim3(a.S), dim3(256), sizeof(int) * kScheduleWords(a.n), a.stream, a.n,
+                           a.P, a.S, a.seg_off, a.peers, a.shift, cl * chunk_cols, static_cast<int>(nclusters),
+                           order);
         if (hipGetLastError() != hipSuccess) { *status = CX_ERR_HIP; return true; }
     }
     int cap = cx_get_tuning(9);
@@ -1065,11 +1161,11 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     if (nt)
         hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, glds, a.stream, op, a.n, a.P, a.S,
                            a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),
-                           static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, slot);
+                           static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, order);
     else
         hipLaunchKernelGGL((gather_kernel<Op, U, false>), grid, block, glds, a.stream, op, a.n, a.P, a.S,
                            a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),
-                           static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, slot);
+                           static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, order);
     *status = hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
     return true;
     }

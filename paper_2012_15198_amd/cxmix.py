@@ -98,10 +98,54 @@ def _stream(stream) -> Optional[int]:
     return getattr(stream, "cuda_stream", stream)
 
 
-def _shape(x):
-    if x.dim() != 2 or x.stride(1) != 1:
-        raise ValueError("expected a row-major [W][ld] tensor (use a view of the padded matrix)")
+def _shape(x, elem_size=4):
+    """(rows, ld) of the matrix that fixes a call's geometry."""
+    _matrix("x_in", x, None, None, elem_size, None)
     return x.shape[0], x.stride(0)
+
+
+def _matrix(name, t, rows, ld, elem_size, like):
+    """The C ABI sees one ld and raw addresses, so a tensor of another shape, stride, element
+    size or device would send the kernels past its allocation: refuse it here."""
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError(f"{name}: expected a row-major [rows][ld] tensor (use a view of the padded matrix)")
+    if t.element_size() != elem_size or (elem_size == 4 and not t.is_floating_point()):
+        raise ValueError(f"{name}: expected {'float32' if elem_size == 4 else '16-bit'} elements, got {t.dtype}")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: expected a device tensor")
+    if rows is not None and t.shape[0] != rows:
+        raise ValueError(f"{name}: expected {rows} rows, got {t.shape[0]}")
+    if ld is not None and t.shape[0] > 1 and t.stride(0) != ld:
+        raise ValueError(f"{name}: row stride {t.stride(0)} differs from x_in's {ld}")
+    if ld is not None and t.shape[1] > ld:
+        raise ValueError(f"{name}: rows longer than the leading dimension")
+    if like is not None and t.device != like.device:
+        raise ValueError(f"{name}: on {t.device}, x_in on {like.device}")
+
+
+def _vector(name, t, n, dtype_size, like, integer=False):
+    if t.dim() != 1 or (t.numel() > 1 and t.stride(0) != 1) or t.numel() < n:
+        raise ValueError(f"{name}: expected a contiguous vector of at least {n} elements")
+    if t.element_size() != dtype_size or t.is_floating_point() == integer:
+        raise ValueError(f"{name}: unexpected element type {t.dtype}")
+    if not t.is_cuda or t.device != like.device:
+        raise ValueError(f"{name}: expected a tensor on {like.device}")
+
+
+def _tables(x_in, P, seg_off_dev, peers_dev, n):
+    """S, after checking the device tables' types and sizes (their CONTENT is checked on the host
+    mirrors by cx_check_segments / cx_check_peers)."""
+    if seg_off_dev.dim() != 1 or seg_off_dev.numel() < 2:
+        raise ValueError("seg_off_dev: expected int64 [S+1]")
+    S = seg_off_dev.numel() - 1
+    _vector("seg_off_dev", seg_off_dev, S + 1, 8, x_in, integer=True)
+    if peers_dev is not None:
+        if not peers_dev.is_contiguous() or peers_dev.numel() != S * n:
+            raise ValueError(f"peers_dev: expected a contiguous int32 [S={S}][n={n}] table")
+        _vector("peers_dev", peers_dev.reshape(-1), S * n, 4, x_in, integer=True)
+    if P < 1 or P > x_in.shape[1]:
+        raise ValueError("P must lie in [1, row length]")
+    return S
 
 
 # ----------------------------------------------------------------------------- host calls
@@ -146,17 +190,17 @@ def cx_get_tuning(key: int) -> int:
 # --------------------------------------------------------------------------- device calls
 def cx_gossip_mix(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int = 0, stream=None):
     W, ld = _shape(x_in)
-    S = seg_off_dev.numel() - 1
+    _matrix("x_out", x_out, W, ld, 4, x_in)
+    S = _tables(x_in, P, seg_off_dev, peers_dev, W)
     _ok("cx_gossip_mix", lib().cx_gossip_mix(_dptr(x_in), _dptr(x_out), ld, W, P, S,
                                              _dptr(seg_off_dev), _dptr(peers_dev), flags,
                                              _stream(stream)))
 
 
 def _mix16(name, x_in, x_out, P, seg_off_dev, peers_dev, flags, stream):
-    W, ld = _shape(x_in)
-    if x_in.element_size() != 2 or x_out.element_size() != 2:
-        raise ValueError("expected 16-bit elements")
-    S = seg_off_dev.numel() - 1
+    W, ld = _shape(x_in, 2)
+    _matrix("x_out", x_out, W, ld, 2, x_in)
+    S = _tables(x_in, P, seg_off_dev, peers_dev, W)
     _ok(name, getattr(lib(), name)(_dptr(x_in), _dptr(x_out), ld, W, P, S, _dptr(seg_off_dev),
                                    _dptr(peers_dev), flags, _stream(stream)))
 
@@ -171,14 +215,18 @@ def cx_gossip_mix_f16(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int = 
     _mix16("cx_gossip_mix_f16", x_in, x_out, P, seg_off_dev, peers_dev, flags, stream)
 
 
+def _leaders(W, G):
+    if G < 1 or W % G:
+        raise ValueError("G must divide the number of rows")
+    return W // G
+
+
 def _hier16(name, x_in, x_out, P, G, seg_off_dev, leader_peers_dev, flags, stream):
-    W, ld = _shape(x_in)
-    if x_in.element_size() != 2 or x_out.element_size() != 2:
-        raise ValueError("expected 16-bit elements")
-    S = seg_off_dev.numel() - 1
+    W, ld = _shape(x_in, 2)
+    _matrix("x_out", x_out, W, ld, 2, x_in)
+    S = _tables(x_in, P, seg_off_dev, leader_peers_dev, _leaders(W, G))
     _ok(name, getattr(lib(), name)(_dptr(x_in), _dptr(x_out), ld, W, P, G, S, _dptr(seg_off_dev),
-                                   _dptr(leader_peers_dev) if leader_peers_dev is not None else None,
-                                   flags, _stream(stream)))
+                                   _dptr(leader_peers_dev), flags, _stream(stream)))
 
 
 def cx_hier_mix_bf16(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flags: int = 0, stream=None):
@@ -194,7 +242,8 @@ def cx_hier_mix_f16(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, 
 def cx_hier_mix(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flags: int = 0,
                 stream=None):
     W, ld = _shape(x_in)
-    S = seg_off_dev.numel() - 1
+    _matrix("x_out", x_out, W, ld, 4, x_in)
+    S = _tables(x_in, P, seg_off_dev, leader_peers_dev, _leaders(W, G))
     _ok("cx_hier_mix", lib().cx_hier_mix(_dptr(x_in), _dptr(x_out), ld, W, P, G, S,
                                          _dptr(seg_off_dev), _dptr(leader_peers_dev), flags,
                                          _stream(stream)))
@@ -203,6 +252,13 @@ def cx_hier_mix(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flag
 def cx_pushsum_mix(x_in, x_out, w_in, w_out, z_out, P: int, hop: int, flags: int = 0,
                    stream=None):
     W, ld = _shape(x_in)
+    _matrix("x_out", x_out, W, ld, 4, x_in)
+    if z_out is not None:
+        _matrix("z_out", z_out, W, ld, 4, x_in)
+    _vector("w_in", w_in, W, 4, x_in)
+    _vector("w_out", w_out, W, 4, x_in)
+    if P < 1 or P > x_in.shape[1]:
+        raise ValueError("P must lie in [1, row length]")
     _ok("cx_pushsum_mix", lib().cx_pushsum_mix(_dptr(x_in), _dptr(x_out), _dptr(w_in),
                                                _dptr(w_out), _dptr(z_out), ld, W, P, hop, flags,
                                                _stream(stream)))
@@ -211,7 +267,9 @@ def cx_pushsum_mix(x_in, x_out, w_in, w_out, z_out, P: int, hop: int, flags: int
 def cx_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: float, P: int,
                      seg_off_dev, peers_dev, flags: int = 0, stream=None):
     W, ld = _shape(x_in)
-    S = seg_off_dev.numel() - 1
+    for name, t in (("x_out", x_out), ("v_in", v_in), ("v_out", v_out), ("g", g)):
+        _matrix(name, t, W, ld, 4, x_in)
+    S = _tables(x_in, P, seg_off_dev, peers_dev, W)
     _ok("cx_sgd_fused_mix", lib().cx_sgd_fused_mix(_dptr(x_in), _dptr(x_out), _dptr(v_in),
                                                    _dptr(v_out), _dptr(g), lr, mu, wd, ld, W, P,
                                                    S, _dptr(seg_off_dev), _dptr(peers_dev), flags,
@@ -222,9 +280,10 @@ def cx_hier_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd:
                           G: int, seg_off_dev, leader_peers_dev, flags: int = 0, stream=None):
     """x, g: [W][ld]; v: [W/G][ld] with the same ld (see include/cx_mix.h)."""
     W, ld = _shape(x_in)
-    if v_in.dim() != 2 or v_in.stride(0) != ld or g.stride(0) != ld:
-        raise ValueError("x, v and g must share one leading dimension")
-    S = seg_off_dev.numel() - 1
+    L = _leaders(W, G)
+    for name, t, rows in (("x_out", x_out, W), ("g", g, W), ("v_in", v_in, L), ("v_out", v_out, L)):
+        _matrix(name, t, rows, ld, 4, x_in)
+    S = _tables(x_in, P, seg_off_dev, leader_peers_dev, L)
     _ok("cx_hier_sgd_fused_mix", lib().cx_hier_sgd_fused_mix(
         _dptr(x_in), _dptr(x_out), _dptr(v_in), _dptr(v_out), _dptr(g), lr, mu, wd, ld, W, P, G, S,
         _dptr(seg_off_dev), _dptr(leader_peers_dev), flags, _stream(stream)))

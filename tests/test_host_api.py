@@ -140,7 +140,7 @@ def test_mix_calls_reject_bad_arguments_on_the_host():
     assert hfused(x_out=B) == -6                       # x out of place but v in place
     assert hfused(v_out=E) == -6                       # v out of place but x in place
     assert hfused(v_in=A, v_out=A) == -6 and hfused(g=A) == -6 and hfused(g=C) == -6
-    assert hfused(G=16, W=32) == -8 and hfused(g=D + 4) == -5
+    assert hfused(G=32, W=64) == -8 and hfused(g=D + 4) == -5
 
     def bf16(fn=None, **kw):
         a = {**ok, **kw}
