@@ -242,6 +242,8 @@ def main():
     ap.add_argument("--no-copy", action="store_true")
     ap.add_argument("--bf16", action="store_true", help="bfloat16 rows: cx_gossip_mix_bf16 / cx_hier_mix_bf16")
     ap.add_argument("--f16", action="store_true", help="binary16 rows: cx_gossip_mix_f16 / cx_hier_mix_f16")
+    ap.add_argument("--tune", default="", metavar="KEY=VALUE[,KEY=VALUE...]",
+                    help="launch parameters for cx_set_tuning (see include/cx_mix.h), e.g. 6=8,1=4")
     ap.add_argument("--in-place", action="store_true",
                     help="update the matrix in place (cycle-walk kernel) instead of ping-pong buffers")
     args = ap.parse_args()
@@ -254,6 +256,11 @@ def main():
     from paper_2012_15198_amd import cxmix as cx
     from paper_2012_15198_amd import workloads as WL
     cx.lib()                                            # fail loudly if the library is not built
+    tuning = {}
+    for item in filter(None, args.tune.split(",")):
+        k, v = item.split("=")
+        cx.cx_set_tuning(int(k), int(v))
+        tuning[int(k)] = int(v)
 
     wl = WL.WORKLOADS[args.workload]
     kind = args.kind or {"gossip": "gossip", "hier": "hier", "fused+pushsum": "fused"}[wl.kind]
@@ -276,7 +283,8 @@ def main():
                        kind, f"cx_{kind}_mix" + ("_" + rows16 if rows16 else "")),
                    "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
                    "buffers": "in place" if args.in_place else "ping-pong (x_in -> x_out, swapped every round)",
-                   "step": "cx_topology_gen(1 round) + table upload + one mixing launch"},
+                   "step": "cx_topology_gen(1 round) + table upload + one mixing launch",
+                   "tuning": tuning or "defaults"},
         "params_mixed_per_s": res["params_mixed_per_s"],
         "frac_of_hbm_peak": res["GBps"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": res["kernel_GBps"], "peak": HBM_PEAK_GBPS,

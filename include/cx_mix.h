@@ -30,7 +30,9 @@
  *              after round); partial overlap is CX_ERR_ALIAS.  Either way every value is
  *              computed from the round's input rows (Algorithm 1 posts every send before
  *              any averaging), every element is read from HBM once and written once, and
- *              the results are bit-identical.  The two cases run different kernels:
+ *              for peer tables that are permutations the results are bit-identical (a table
+ *              that is not a permutation is honoured out of place only: see "peer table").
+ *              The two cases run different kernels:
  *              in place, one wavefront owns a column tile and walks the rows along the
  *              cycles of the peer permutation; out of place, one short workgroup per
  *              (row, column chunk) reads the row and its peer and writes the result --
@@ -90,7 +92,7 @@ enum cx_topology_mode {
 /* Human-readable name of a status code (static storage). */
 const char *cx_status_string(int status);
 
-/* ABI version of this header (bumped on any signature change). */
+/* ABI version of this header (bumped on any signature change): 2. */
 int cx_abi_version(void);
 
 /* ------------------------------------------------------------------------------------
@@ -109,7 +111,8 @@ int cx_abi_version(void);
  *   mode 2  the conventional random topology the paper compares with (Sections 3.2, 4.3):
  *           row i draws uniformly among the other n-1 rows (draw index i), independently of
  *           the other rows, so a row may be chosen several times or never.  Such a table is
- *           not a permutation: mix with it out of place.
+ *           not a permutation: mix with it OUT OF PLACE only (in place it would leave every
+ *           segment unmixed; see cx_check_peers).
  *   | 16    every segment of a round gets segment 0's table, which equals model-wise
  *           communication (Section 3; the "without segment-wise" ablation of Section 4.3).
  *   peers_host  int32 [R][S][n], caller-allocated, written completely on success.
@@ -119,10 +122,24 @@ int cx_abi_version(void);
 int cx_topology_gen(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t R,
                     int32_t mode, int32_t *peers_host);
 
-/* Host-side checks of the host mirrors of the device tables (Section 3.2: every row is
- * chosen exactly once and nobody chooses itself).  peers_host is int32 [S][n]. */
+/* Host-side checks of the host mirrors of the device tables.  The mixing calls never read a
+ * device table on the host (that would need a synchronisation), so a caller validates the
+ * host copy before uploading it.
+ * cx_check_segments: 0 = seg_off[0] <= seg_off[1] <= ... <= seg_off[S] = P, else CX_ERR_SEGMENTS.
+ * cx_check_peers: peers_host is int32 [S][n]; `mode` names the kind of table, which is also what
+ * the two kernels accept:
+ *   CX_TOPO_FAIR, CX_TOPO_DIRECTED_EXP  every peers[s] is a permutation of 0..n-1 without a fixed
+ *       point (Section 3.2: every row is chosen exactly once and nobody chooses itself).  This is
+ *       what a call that updates its matrix IN PLACE needs: in place, a segment whose table is not
+ *       a permutation is left unmixed (the call still returns CX_OK: it cannot look).
+ *   CX_TOPO_UNFAIR  entries in [0, n), no row names itself, duplicates allowed (the random
+ *       topology without fair peer selection of Sections 3.2 / 4.3).  Such a table is served as
+ *       written by calls whose output buffers differ from their input buffers, and ONLY by them.
+ * OR-ing CX_TOPO_SAME_ALL_SEGMENTS into mode additionally requires all S tables to be equal.
+ * Returns CX_ERR_PEERS for a table that fails its mode's test, CX_ERR_UNSUPPORTED for an unknown
+ * mode, CX_ERR_NULL / CX_ERR_SHAPE (S < 1, n < 2, n > CX_MAX_ROWS) as usual. */
 int cx_check_segments(const int64_t *seg_off_host, int32_t S, int64_t P);
-int cx_check_peers(const int32_t *peers_host, int32_t S, int32_t n);
+int cx_check_peers(const int32_t *peers_host, int32_t S, int32_t n, int32_t mode);
 
 /* ------------------------------------------------------------------------------------
  * cx_gossip_mix -- Algorithm 1, averaging step, for all W rows at once:

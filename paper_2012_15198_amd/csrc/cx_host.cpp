@@ -96,7 +96,7 @@ const char *cx_status_string(int status)
     }
 }
 
-int cx_abi_version(void) { return 1; }
+int cx_abi_version(void) { return 2; }
 
 int cx_topology_gen(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t R,
                     int32_t mode, int32_t *peers_host)
@@ -143,19 +143,25 @@ int cx_check_segments(const int64_t *seg_off_host, int32_t S, int64_t P)
     return CX_OK;
 }
 
-int cx_check_peers(const int32_t *peers_host, int32_t S, int32_t n)
+int cx_check_peers(const int32_t *peers_host, int32_t S, int32_t n, int32_t mode)
 {
     if (!peers_host) return CX_ERR_NULL;
     if (S < 1 || n < 2 || n > CX_MAX_ROWS) return CX_ERR_SHAPE;
+    const bool same_for_all_segments = (mode & CX_TOPO_SAME_ALL_SEGMENTS) != 0;
+    mode &= ~CX_TOPO_SAME_ALL_SEGMENTS;
+    if (mode != CX_TOPO_FAIR && mode != CX_TOPO_DIRECTED_EXP && mode != CX_TOPO_UNFAIR) return CX_ERR_UNSUPPORTED;
+    const bool duplicates_allowed = mode == CX_TOPO_UNFAIR;
     std::vector<uint8_t> seen(n);
     for (int32_t s = 0; s < S; ++s) {
         std::fill(seen.begin(), seen.end(), 0);
         const int32_t *row = peers_host + static_cast<int64_t>(s) * n;
         for (int32_t i = 0; i < n; ++i) {
             const int32_t j = row[i];
-            if (j < 0 || j >= n || j == i || seen[j]) return CX_ERR_PEERS;
+            if (j < 0 || j >= n || j == i) return CX_ERR_PEERS;
+            if (seen[j] && !duplicates_allowed) return CX_ERR_PEERS;
             seen[j] = 1;
         }
+        if (same_for_all_segments && s > 0 && !std::equal(row, row + n, peers_host)) return CX_ERR_PEERS;
     }
     return CX_OK;
 }

@@ -957,10 +957,10 @@ struct MixArgs {
     hipStream_t stream;
     bool out_of_place;          // every output buffer is distinct from its input buffer
     int rows_per_gossip_row;    // G: matrix rows behind one gossiping row (cluster footprint)
-    // Row-order table supplied by the entry point (device address and capacity in words) instead
-    // of one of the library's per-stream slots; the call then fails with CX_ERR_SHAPE rather than
-    // run without a table when the workload's table does not fit.
-    unsigned *order_table = nullptr;
+    // Row-order table supplied by the entry point instead of one of the library's per-stream
+    // slots: its capacity in words and where to get its device address once the workload is known
+    // to fit (the call fails with CX_ERR_SHAPE rather than run without a table when it does not).
+    unsigned *(*order_provider)() = nullptr;
     int64_t order_entries = 0;
 };
 
@@ -1098,18 +1098,17 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     // Rows in cycle order pay when the partner's fetch has to be kept out of HBM; a matrix that
     // the last-level cache holds whole gains nothing from the extra launch.
     const int64_t matrix_bytes = static_cast<int64_t>(a.n) * a.rows_per_gossip_row * a.P * (16 / Op::kElems);
-    bool ordered = cx_get_tuning(8) != 0 && a.n > 1 && a.S <= 4096 &&
-                   (a.order_table || cx_get_tuning(8) == 1 || matrix_bytes > (64LL << 20));
+    const bool own_table = a.order_provider != nullptr;
+    bool ordered = a.n > 1 && a.S <= 4096 &&
+                   (own_table || cx_get_tuning(8) == 1 || (cx_get_tuning(8) != 0 && matrix_bytes > (64LL << 20)));
+    if (own_table && !ordered) { *status = CX_ERR_SHAPE; return true; }
     std::lock_guard<std::mutex> enqueue_lock(enqueue_mutex());
     unsigned *order = nullptr;
-    int64_t order_entries = kOrderEntries;
-    if (ordered && a.order_table) {
-        order = a.order_table;
-        order_entries = a.order_entries;
-    } else if (ordered) {
+    const int64_t order_entries = own_table ? a.order_entries : kOrderEntries;
+    if (ordered && !own_table) {
         order = order_table_for(a.stream);
+        if (!order) ordered = false;
     }
-    if (!order) ordered = false;
     int64_t cl = cl_req;
     if (cl < 1) {
         // ordered rows: the operator's visit length per XCD (shorter visits lose DRAM row
@@ -1121,11 +1120,11 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     }
     if (ordered) {                                // the order table must fit its slot
         const int64_t max_clusters = order_entries / a.n - nxcd;
-        if (max_clusters < 1) { if (a.order_table) { *status = CX_ERR_SHAPE; return true; } ordered = false; }
+        if (max_clusters < 1) { if (own_table) { *status = CX_ERR_SHAPE; return true; } ordered = false; }
         else {
             const int64_t min_cl = (nchunks + max_clusters - 1) / max_clusters;
             if (cl < min_cl) {
-                if (a.order_table) { *status = CX_ERR_SHAPE; return true; }   // beyond the stated maximum
+                if (own_table) { *status = CX_ERR_SHAPE; return true; }       // beyond the stated maximum
                 cl = min_cl;
             }
         }
@@ -1140,7 +1139,7 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     // the kernel numbers chunks and tiles, the grid's padding included, in 32 bits
     if ((clusters * nxcd * cl + 1) * waves > 0x7fffffffLL) { *status = CX_ERR_SHAPE; return true; }
     if (ordered && clusters * nxcd * a.n > order_entries) {        // table too large: natural row order
-        if (a.order_table) { *status = CX_ERR_SHAPE; return true; }
+        if (own_table) { *status = CX_ERR_SHAPE; return true; }
         ordered = false;
     }
     const dim3 grid(static_cast<unsigned>(cl * nxcd), static_cast<unsigned>(a.n),
@@ -1148,6 +1147,10 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     const dim3 block(kWave * waves);
     const int xcd_shift = xcd_aware ? 3 : 0;
     if (!ordered) order = nullptr;
+    if (ordered && own_table) {
+        order = a.order_provider();
+        if (!order) { *status = CX_ERR_HIP; return true; }
+    }
     if (ordered) {
         const int64_t nclusters = clusters * nxcd;
         hipLaunchKernelGGL(order_kernel, dim3(a.S), dim3(256), sizeof(int) * kScheduleWords(a.n), a.stream, a.n,

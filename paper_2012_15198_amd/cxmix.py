@@ -59,7 +59,7 @@ def lib() -> ctypes.CDLL:
     L.cx_abi_version.argtypes = []
     L.cx_topology_gen.argtypes = [u64, i32, i32, i32, i32, i32, vp]
     L.cx_check_segments.argtypes = [vp, i32, i64]
-    L.cx_check_peers.argtypes = [vp, i32, i32]
+    L.cx_check_peers.argtypes = [vp, i32, i32, i32]
     L.cx_gossip_mix.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
     L.cx_gossip_mix_bf16.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
     L.cx_gossip_mix_f16.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
@@ -100,36 +100,30 @@ def _stream(stream) -> Optional[int]:
 
 def _shape(x, elem_size=4):
     """(rows, ld) of the matrix that fixes a call's geometry."""
-    _matrix("x_in", x, None, None, elem_size, None)
+    _matrix("x_in", x, None, None, elem_size)
     return x.shape[0], x.stride(0)
 
 
-def _matrix(name, t, rows, ld, elem_size, like):
-    """The C ABI sees one ld and raw addresses, so a tensor of another shape, stride, element
-    size or device would send the kernels past its allocation: refuse it here."""
+def _matrix(name, t, rows, ld, elem_size):
+    """The C ABI sees one ld and raw addresses, so a tensor of another shape, stride or element
+    size would send the kernels past its allocation: refuse it here."""
     if t.dim() != 2 or t.stride(1) != 1:
         raise ValueError(f"{name}: expected a row-major [rows][ld] tensor (use a view of the padded matrix)")
     if t.element_size() != elem_size or (elem_size == 4 and not t.is_floating_point()):
         raise ValueError(f"{name}: expected {'float32' if elem_size == 4 else '16-bit'} elements, got {t.dtype}")
-    if not t.is_cuda:
-        raise ValueError(f"{name}: expected a device tensor")
     if rows is not None and t.shape[0] != rows:
         raise ValueError(f"{name}: expected {rows} rows, got {t.shape[0]}")
     if ld is not None and t.shape[0] > 1 and t.stride(0) != ld:
         raise ValueError(f"{name}: row stride {t.stride(0)} differs from x_in's {ld}")
     if ld is not None and t.shape[1] > ld:
         raise ValueError(f"{name}: rows longer than the leading dimension")
-    if like is not None and t.device != like.device:
-        raise ValueError(f"{name}: on {t.device}, x_in on {like.device}")
 
 
-def _vector(name, t, n, dtype_size, like, integer=False):
+def _vector(name, t, n, elem_size, integer=False):
     if t.dim() != 1 or (t.numel() > 1 and t.stride(0) != 1) or t.numel() < n:
         raise ValueError(f"{name}: expected a contiguous vector of at least {n} elements")
-    if t.element_size() != dtype_size or t.is_floating_point() == integer:
+    if t.element_size() != elem_size or t.is_floating_point() == integer:
         raise ValueError(f"{name}: unexpected element type {t.dtype}")
-    if not t.is_cuda or t.device != like.device:
-        raise ValueError(f"{name}: expected a tensor on {like.device}")
 
 
 def _tables(x_in, P, seg_off_dev, peers_dev, n):
@@ -138,14 +132,26 @@ def _tables(x_in, P, seg_off_dev, peers_dev, n):
     if seg_off_dev.dim() != 1 or seg_off_dev.numel() < 2:
         raise ValueError("seg_off_dev: expected int64 [S+1]")
     S = seg_off_dev.numel() - 1
-    _vector("seg_off_dev", seg_off_dev, S + 1, 8, x_in, integer=True)
+    _vector("seg_off_dev", seg_off_dev, S + 1, 8, integer=True)
     if peers_dev is not None:
         if not peers_dev.is_contiguous() or peers_dev.numel() != S * n:
             raise ValueError(f"peers_dev: expected a contiguous int32 [S={S}][n={n}] table")
-        _vector("peers_dev", peers_dev.reshape(-1), S * n, 4, x_in, integer=True)
+        _vector("peers_dev", peers_dev.reshape(-1), S * n, 4, integer=True)
     if P < 1 or P > x_in.shape[1]:
         raise ValueError("P must lie in [1, row length]")
     return S
+
+
+def _same_device(*tensors):
+    """Last check before the call: every buffer lives on one GPU."""
+    first = tensors[0]
+    for t in tensors:
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise ValueError("expected device tensors (the mixing calls take device pointers)")
+        if t.device != first.device:
+            raise ValueError(f"buffers on different devices: {t.device} and {first.device}")
 
 
 # ----------------------------------------------------------------------------- host calls
@@ -172,11 +178,14 @@ def cx_check_segments(seg_off_host: np.ndarray, P: int) -> None:
     _ok("cx_check_segments", lib().cx_check_segments(so.ctypes.data, len(so) - 1, P))
 
 
-def cx_check_peers(peers_host: np.ndarray) -> None:
+def cx_check_peers(peers_host: np.ndarray, mode: int = CX_TOPO_FAIR) -> None:
+    """Raises unless one round's [S][n] table is what `mode` promises (see include/cx_mix.h):
+    a fixed-point-free permutation per segment, or, for CX_TOPO_UNFAIR, entries in range that never
+    name their own row (then mix out of place)."""
     p = np.ascontiguousarray(peers_host, dtype=np.int32)
     if p.ndim != 2:
         raise ValueError("expected one round's [S][n] table")
-    _ok("cx_check_peers", lib().cx_check_peers(p.ctypes.data, p.shape[0], p.shape[1]))
+    _ok("cx_check_peers", lib().cx_check_peers(p.ctypes.data, p.shape[0], p.shape[1], mode))
 
 
 def cx_set_tuning(key: int, value: int) -> None:
@@ -190,8 +199,9 @@ def cx_get_tuning(key: int) -> int:
 # --------------------------------------------------------------------------- device calls
 def cx_gossip_mix(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int = 0, stream=None):
     W, ld = _shape(x_in)
-    _matrix("x_out", x_out, W, ld, 4, x_in)
+    _matrix("x_out", x_out, W, ld, 4)
     S = _tables(x_in, P, seg_off_dev, peers_dev, W)
+    _same_device(x_in, x_out, seg_off_dev, peers_dev)
     _ok("cx_gossip_mix", lib().cx_gossip_mix(_dptr(x_in), _dptr(x_out), ld, W, P, S,
                                              _dptr(seg_off_dev), _dptr(peers_dev), flags,
                                              _stream(stream)))
@@ -199,8 +209,9 @@ def cx_gossip_mix(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int = 0, s
 
 def _mix16(name, x_in, x_out, P, seg_off_dev, peers_dev, flags, stream):
     W, ld = _shape(x_in, 2)
-    _matrix("x_out", x_out, W, ld, 2, x_in)
+    _matrix("x_out", x_out, W, ld, 2)
     S = _tables(x_in, P, seg_off_dev, peers_dev, W)
+    _same_device(x_in, x_out, seg_off_dev, peers_dev)
     _ok(name, getattr(lib(), name)(_dptr(x_in), _dptr(x_out), ld, W, P, S, _dptr(seg_off_dev),
                                    _dptr(peers_dev), flags, _stream(stream)))
 
@@ -223,8 +234,9 @@ def _leaders(W, G):
 
 def _hier16(name, x_in, x_out, P, G, seg_off_dev, leader_peers_dev, flags, stream):
     W, ld = _shape(x_in, 2)
-    _matrix("x_out", x_out, W, ld, 2, x_in)
+    _matrix("x_out", x_out, W, ld, 2)
     S = _tables(x_in, P, seg_off_dev, leader_peers_dev, _leaders(W, G))
+    _same_device(x_in, x_out, seg_off_dev, leader_peers_dev)
     _ok(name, getattr(lib(), name)(_dptr(x_in), _dptr(x_out), ld, W, P, G, S, _dptr(seg_off_dev),
                                    _dptr(leader_peers_dev), flags, _stream(stream)))
 
@@ -242,8 +254,9 @@ def cx_hier_mix_f16(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, 
 def cx_hier_mix(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flags: int = 0,
                 stream=None):
     W, ld = _shape(x_in)
-    _matrix("x_out", x_out, W, ld, 4, x_in)
+    _matrix("x_out", x_out, W, ld, 4)
     S = _tables(x_in, P, seg_off_dev, leader_peers_dev, _leaders(W, G))
+    _same_device(x_in, x_out, seg_off_dev, leader_peers_dev)
     _ok("cx_hier_mix", lib().cx_hier_mix(_dptr(x_in), _dptr(x_out), ld, W, P, G, S,
                                          _dptr(seg_off_dev), _dptr(leader_peers_dev), flags,
                                          _stream(stream)))
@@ -252,13 +265,14 @@ def cx_hier_mix(x_in, x_out, P: int, G: int, seg_off_dev, leader_peers_dev, flag
 def cx_pushsum_mix(x_in, x_out, w_in, w_out, z_out, P: int, hop: int, flags: int = 0,
                    stream=None):
     W, ld = _shape(x_in)
-    _matrix("x_out", x_out, W, ld, 4, x_in)
+    _matrix("x_out", x_out, W, ld, 4)
     if z_out is not None:
-        _matrix("z_out", z_out, W, ld, 4, x_in)
-    _vector("w_in", w_in, W, 4, x_in)
-    _vector("w_out", w_out, W, 4, x_in)
+        _matrix("z_out", z_out, W, ld, 4)
+    _vector("w_in", w_in, W, 4)
+    _vector("w_out", w_out, W, 4)
     if P < 1 or P > x_in.shape[1]:
         raise ValueError("P must lie in [1, row length]")
+    _same_device(x_in, x_out, w_in, w_out, z_out)
     _ok("cx_pushsum_mix", lib().cx_pushsum_mix(_dptr(x_in), _dptr(x_out), _dptr(w_in),
                                                _dptr(w_out), _dptr(z_out), ld, W, P, hop, flags,
                                                _stream(stream)))
@@ -268,8 +282,9 @@ def cx_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: floa
                      seg_off_dev, peers_dev, flags: int = 0, stream=None):
     W, ld = _shape(x_in)
     for name, t in (("x_out", x_out), ("v_in", v_in), ("v_out", v_out), ("g", g)):
-        _matrix(name, t, W, ld, 4, x_in)
+        _matrix(name, t, W, ld, 4)
     S = _tables(x_in, P, seg_off_dev, peers_dev, W)
+    _same_device(x_in, x_out, v_in, v_out, g, seg_off_dev, peers_dev)
     _ok("cx_sgd_fused_mix", lib().cx_sgd_fused_mix(_dptr(x_in), _dptr(x_out), _dptr(v_in),
                                                    _dptr(v_out), _dptr(g), lr, mu, wd, ld, W, P,
                                                    S, _dptr(seg_off_dev), _dptr(peers_dev), flags,
@@ -282,13 +297,19 @@ def cx_hier_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd:
     W, ld = _shape(x_in)
     L = _leaders(W, G)
     for name, t, rows in (("x_out", x_out, W), ("g", g, W), ("v_in", v_in, L), ("v_out", v_out, L)):
-        _matrix(name, t, rows, ld, 4, x_in)
+        _matrix(name, t, rows, ld, 4)
     S = _tables(x_in, P, seg_off_dev, leader_peers_dev, L)
+    _same_device(x_in, x_out, v_in, v_out, g, seg_off_dev, leader_peers_dev)
     _ok("cx_hier_sgd_fused_mix", lib().cx_hier_sgd_fused_mix(
         _dptr(x_in), _dptr(x_out), _dptr(v_in), _dptr(v_out), _dptr(g), lr, mu, wd, ld, W, P, G, S,
         _dptr(seg_off_dev), _dptr(leader_peers_dev), flags, _stream(stream)))
 
 
 def cx_copy_baseline(src, dst, stream=None):
+    if src.element_size() != 4 or dst.element_size() != 4 or dst.numel() < src.numel():
+        raise ValueError("expected float32 buffers, dst at least as long as src")
+    if not (src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("expected contiguous buffers")
+    _same_device(src, dst)
     _ok("cx_copy_baseline", lib().cx_copy_baseline(_dptr(src), _dptr(dst), src.numel(),
                                                    _stream(stream)))

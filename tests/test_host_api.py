@@ -22,7 +22,7 @@ def test_library_exports_every_symbol_the_header_declares():
     L = cx.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert cx.cx_abi_version() == 1
+    assert cx.cx_abi_version() == 2
     assert cx.cx_status_string(0) == "CX_OK" and cx.cx_status_string(-6) == "CX_ERR_ALIAS"
     for code, name in cx.STATUS.items():
         assert cx.cx_status_string(code) == name
@@ -78,6 +78,36 @@ def test_check_segments_and_peers():
         with pytest.raises(cx.CxError) as e:
             cx.cx_check_peers(np.array(bad))
         assert e.value.status == -4
+
+
+def test_check_peers_modes_say_which_kernel_accepts_a_table():
+    """A table without fair selection (duplicates) passes only the mode that the out-of-place calls
+    serve; the model-wise flag requires equal tables; every generated table passes its own mode."""
+    dup = np.array([[1, 0, 0, 1], [3, 3, 1, 0]])
+    cx.cx_check_peers(dup, cx.CX_TOPO_UNFAIR)
+    for mode in (cx.CX_TOPO_FAIR, cx.CX_TOPO_DIRECTED_EXP):
+        with pytest.raises(cx.CxError) as e:
+            cx.cx_check_peers(dup, mode)
+        assert e.value.status == -4
+    for bad in ([[0, 0, 1]], [[1, 2, 3]], [[1, -1, 0]]):           # own row, out of range
+        with pytest.raises(cx.CxError) as e:
+            cx.cx_check_peers(np.array(bad), cx.CX_TOPO_UNFAIR)
+        assert e.value.status == -4
+    with pytest.raises(cx.CxError) as e:
+        cx.cx_check_peers(dup, 3)
+    assert e.value.status == -8
+    same = np.array([[1, 2, 0], [1, 2, 0]])
+    cx.cx_check_peers(same, cx.CX_TOPO_FAIR | cx.CX_TOPO_SAME_ALL_SEGMENTS)
+    with pytest.raises(cx.CxError):
+        cx.cx_check_peers(np.array([[1, 2, 0], [2, 0, 1]]), cx.CX_TOPO_FAIR | cx.CX_TOPO_SAME_ALL_SEGMENTS)
+    for mode in (0, 1, 2, 16, 18):
+        for tab in cx.cx_topology_gen(7, 12, 4, 0, 6, mode):
+            cx.cx_check_peers(tab, mode)
+    unfair = cx.cx_topology_gen(7, 12, 4, 0, 6, cx.CX_TOPO_UNFAIR)
+    assert any(len(set(t)) < 12 for tab in unfair for t in tab.tolist())      # duplicates do occur ...
+    with pytest.raises(cx.CxError):                                            # ... and the fair test refuses them
+        for tab in unfair:
+            cx.cx_check_peers(tab, cx.CX_TOPO_FAIR)
 
 
 def test_mix_calls_reject_bad_arguments_on_the_host():
@@ -200,11 +230,11 @@ int main(void)
     int32_t peers[R * S * N];
     int64_t seg_off[S + 1] = {0, 10, 20, 30};
     int r, s, i, rc;
-    if (cx_abi_version() < 1) return 10;
+    if (cx_abi_version() != 2) return 10;
     rc = cx_topology_gen(2u, N, S, 0, R, CX_TOPO_FAIR, peers);
     if (rc != CX_OK) return 11;
     for (r = 0; r < R; ++r)
-        if (cx_check_peers(peers + r * S * N, S, N) != CX_OK) return 12;
+        if (cx_check_peers(peers + r * S * N, S, N, CX_TOPO_FAIR) != CX_OK) return 12;
     if (cx_check_segments(seg_off, S, 30) != CX_OK) return 13;
     if (cx_check_segments(seg_off, S, 31) != CX_ERR_SEGMENTS) return 14;
     if (cx_gossip_mix(NULL, NULL, 32, N, 30, S, NULL, NULL, 0u, NULL) != CX_ERR_NULL) return 15;

@@ -36,6 +36,62 @@ def test_key_and_draw_are_counter_based():
     assert O.key(42, 1, 2) != O.key(43, 1, 2) != O.key(42, 2, 1)
 
 
+def _mix(z):
+    """The bit mixer in Python integers: xor-shift 30, multiply, xor-shift 27, multiply, xor-shift 31."""
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M64
+    return z ^ (z >> 31)
+
+
+def _key(seed, rnd, seg):
+    """The frozen key function, from its statement: mix(mix(mix(seed + gamma) + round) + segment)."""
+    return _mix((_mix((_mix((seed + GAMMA) & M64) + rnd) & M64) + seg) & M64)
+
+
+def test_key_and_draw_printed_vectors(golden_dir):
+    """The key of a (seed, round, segment) topology and its draws, recomputed here in Python integers
+    from the statement of the generator and compared with the stored vectors and with the oracle.  The
+    vectors hold (round, segment) = (1, 2) next to (2, 1): swapping the two fields fails."""
+    rows = [l for l in open(os.path.join(golden_dir, "key_draw_vectors.txt")) if not l.startswith("#")]
+    assert len(rows) >= 8
+    keys = {}
+    for line in rows:
+        head, tail = line.split(":")
+        seed, rnd, seg = map(int, head.split())
+        k, *draws = (int(h, 16) for h in tail.split())
+        assert _key(seed, rnd, seg) == k == O.key(seed, rnd, seg), line
+        for i, want in zip((0, 1, 5, 1024), draws):
+            assert _mix((k + i) & M64) == want == O.draw(k, i), (line, i)
+        keys[(seed, rnd, seg)] = k
+    assert keys[(2, 1, 2)] != keys[(2, 2, 1)] and keys[(2, 0, 3)] != keys[(2, 3, 0)]
+    assert len(set(keys.values())) == len(keys)
+
+
+def test_tables_follow_from_the_python_integer_draws():
+    """Algorithm 2 walked in Python from draws computed in Python integers (no oracle call inside)
+    gives the oracle's tables, for several rounds and segments: the oracle's indexing of round and
+    segment into the key, and of the rank into the draw, is the stated one."""
+    def table(seed, rnd, seg, n):
+        k = _key(seed, rnd, seg)
+        chosen, d = [], []
+        for i in range(n):
+            cand = [j for j in range(n) if j != i and j not in chosen]
+            if not cand:
+                swap = (_mix((k + n) & M64) * (n - 1)) >> 64
+                d.append(d[swap])
+                d[swap] = i
+                break
+            pick = cand[(_mix((k + i) & M64) * len(cand)) >> 64]
+            chosen.append(pick)
+            d.append(pick)
+        return d
+    for seed, n, S, r0, R in [(2, 8, 4, 0, 3), (5, 3, 6, 4, 30), (2**64 - 1, 13, 2, 9, 2)]:
+        got = O.topology(seed, n, S, r0, R)
+        for r in range(R):
+            for s in range(S):
+                assert got[r, s].tolist() == table(seed, r0 + r, s, n), (seed, r, s)
+
+
 def test_uniform_is_floor_of_scaled_product():
     for v, m in [(0, 7), (M64, 7), (2**63, 2), (2**63 - 1, 2), (12345678901234567890, 255),
                  (2**64 // 3, 3), (2**64 // 3 + 1, 3)]:
