@@ -154,6 +154,29 @@ int cx_gossip_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_
                   uint32_t flags, void *stream);
 
 /* ------------------------------------------------------------------------------------
+ * cx_gossip_mix_noalloc -- cx_gossip_mix, out of place, for callers that cannot allocate device
+ * memory or call anything that might: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results; the
+ * difference is where the kernels' scratch (the row-order table) lives: in ONE static device
+ * array of CX_NOALLOC_ORDER_WORDS 32-bit words (1 MiB) per GPU, held until the process ends, whose
+ * address the library asks the runtime for once per device.  The call makes no hipMalloc /
+ * hipFree and no allocating library call; it enqueues two kernels on `stream`.
+ *   x_out must differ from x_in (CX_ERR_ALIAS otherwise: the in-place kernel has no scratch).
+ *   The table needs W words per cluster of 65,536 columns (8 clusters side by side):
+ *   CX_ERR_SHAPE if ceil(P / 1024) > 64 * (CX_NOALLOC_ORDER_WORDS / W - 8), e.g. P > 133 M columns
+ *   at W = 128 or P > 16 M at W = 1024 -- the call never falls back to a slower path silently.
+ *   (Launch parameters changed through cx_set_tuning move this limit.)
+ *   Every call on a GPU uses that GPU's one table, on whatever stream: calls that overlap in time
+ *   on one GPU race on it and give wrong results -- run them in one stream's order.  Nothing
+ *   has to be cleared between calls: a call rewrites every word it reads.
+ * Errors otherwise as cx_gossip_mix; CX_ERR_HIP also if the runtime cannot name the array.
+ */
+#define CX_NOALLOC_ORDER_WORDS (1 << 18)
+int cx_gossip_mix_noalloc(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P,
+                          int32_t S, const int64_t *seg_off_dev, const int32_t *peers_dev,
+                          uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
  * cx_hier_mix -- hierarchical Crossover-SGD (Section 3.3) on parameters: groups are G
  * consecutive rows, the first row of a group is its leader, L = W / G.
  *     m_g  = (pairwise-tree fp32 sum of the G rows of group g) * (1.0f / G)

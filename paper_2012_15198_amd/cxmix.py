@@ -28,7 +28,7 @@ TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE, TUNE_ORDERED, TUNE
 
 EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_segments",
            "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",
-           "cx_sgd_fused_mix", "cx_hier_sgd_fused_mix", "cx_gossip_mix_bf16", "cx_gossip_mix_f16", "cx_hier_mix_bf16", "cx_hier_mix_f16",
+           "cx_sgd_fused_mix", "cx_hier_sgd_fused_mix", "cx_gossip_mix_noalloc", "cx_gossip_mix_bf16", "cx_gossip_mix_f16", "cx_hier_mix_bf16", "cx_hier_mix_f16",
            "cx_copy_baseline", "cx_set_tuning",
            "cx_get_tuning"]
 
@@ -61,6 +61,7 @@ def lib() -> ctypes.CDLL:
     L.cx_check_segments.argtypes = [vp, i32, i64]
     L.cx_check_peers.argtypes = [vp, i32, i32, i32]
     L.cx_gossip_mix.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
+    L.cx_gossip_mix_noalloc.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
     L.cx_gossip_mix_bf16.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
     L.cx_gossip_mix_f16.argtypes = [vp, vp, i64, i32, i64, i32, vp, vp, u32, vp]
     L.cx_hier_mix_bf16.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, u32, vp]
@@ -205,6 +206,17 @@ def cx_gossip_mix(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int = 0, s
     _ok("cx_gossip_mix", lib().cx_gossip_mix(_dptr(x_in), _dptr(x_out), ld, W, P, S,
                                              _dptr(seg_off_dev), _dptr(peers_dev), flags,
                                              _stream(stream)))
+
+
+def cx_gossip_mix_noalloc(x_in, x_out, P: int, seg_off_dev, peers_dev, flags: int = 0, stream=None):
+    """cx_gossip_mix with its scratch in a static device array (out of place only)."""
+    W, ld = _shape(x_in)
+    _matrix("x_out", x_out, W, ld, 4)
+    S = _tables(x_in, P, seg_off_dev, peers_dev, W)
+    _same_device(x_in, x_out, seg_off_dev, peers_dev)
+    _ok("cx_gossip_mix_noalloc", lib().cx_gossip_mix_noalloc(_dptr(x_in), _dptr(x_out), ld, W, P, S,
+                                                             _dptr(seg_off_dev), _dptr(peers_dev), flags,
+                                                             _stream(stream)))
 
 
 def _mix16(name, x_in, x_out, P, seg_off_dev, peers_dev, flags, stream):
