@@ -27,7 +27,10 @@ __all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topo
 
 
 def build_oracle(force: bool = False) -> str:
-    """Compile the oracle with gcc (no FMA contraction, no fast-math)."""
+    """Compile the oracle with gcc (no FMA contraction, no fast-math).  CX_ORACLE_LIB names a build
+    to load instead (the sanitizer test points it at an instrumented one)."""
+    if os.environ.get("CX_ORACLE_LIB"):
+        return os.environ["CX_ORACLE_LIB"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
                                "-fexcess-precision=standard", "-Wall", "-Wextra", "-shared",
