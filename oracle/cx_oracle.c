@@ -26,7 +26,11 @@
  * with mixing off equals torch.optim.SGD; the gradient-reducing hierarchical step
  * with one group equals SGD on the averaged gradient; the bfloat16 and binary16
  * conversions against torch's and numpy's on every bit pattern, their rounding
- * ties, underflow and overflow by hand.  No function here is "parity unpinned".
+ * ties, underflow and overflow by hand; the double -> 16-bit rounding against an exact
+ * rational nearest-value search (every tie, the overflow point, the subnormal range) and
+ * numpy; the optimizer steps on 16-bit rows by hand (one case that tells one rounding from
+ * rounding through fp32), against the fp32-row steps on widened rows and against
+ * torch.optim.SGD.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -545,6 +549,156 @@ int oracle_hier_sgd_fused_mix_f32(const float *x_in, const float *v_in, const fl
         }
     free(h);
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* The optimizer steps on 16-bit rows (Section 4.1 / Table 1: the paper trains  */
+/* in mixed precision).  Reading: the parameters x and the gradients g are held */
+/* in the 16-bit format (fmt 0 = bfloat16, 1 = binary16), the momentum v stays  */
+/* fp32, as mixed-precision optimizers keep their state.  Every input is        */
+/* widened exactly, the step runs in double exactly as above, v' is rounded     */
+/* once to fp32 and x' ONCE to the 16-bit format, straight from the double (not */
+/* through fp32: rounding twice can land on the wrong side of a tie).           */
+/* ------------------------------------------------------------------------- */
+/* double -> 16-bit pattern, nearest, ties to even, straight from the double's own bits.
+ * keep = fraction bits of the target (7 or 10), emin = its smallest normal exponent. */
+static uint16_t round_double_to_16(double d, int keep, int emin, int emax, int bias)
+{
+    uint64_t u;
+    memcpy(&u, &d, sizeof u);
+    uint16_t sign = (uint16_t)((u >> 48) & 0x8000u);
+    uint64_t a = u & 0x7fffffffffffffffULL;
+    uint16_t inf = (uint16_t)(((1u << (15 - keep)) - 1u) << keep);
+    if (a > 0x7ff0000000000000ULL) return (uint16_t)(sign | inf | (1u << (keep - 1)));   /* NaN stays a quiet NaN */
+    if (a == 0x7ff0000000000000ULL) return (uint16_t)(sign | inf);
+    if (a == 0) return sign;
+    int e = (int)(a >> 52) - 1023;                     /* widened 16- and 32-bit values are normal doubles */
+    uint64_t m = (a & 0xfffffffffffffULL) | (1ULL << 52);   /* 53-bit significand, value = m * 2^(e-52) */
+    if ((a >> 52) == 0) { e = -1022; m = a; }          /* a subnormal double: far below both formats */
+    /* the unit of the result: 2^(e-keep) for a normal result, 2^(emin-keep) in the subnormal range */
+    int drop = 52 - keep + (e < emin ? emin - e : 0);   /* low bits of m that fall below that unit */
+    uint64_t q, rest, half;
+    if (drop >= 64) { q = 0; rest = 1; half = 2; }      /* far below half a unit */
+    else {
+        q = m >> drop;
+        rest = m & ((1ULL << drop) - 1ULL);
+        half = 1ULL << (drop - 1);
+    }
+    if (rest > half || (rest == half && (q & 1ULL))) ++q;
+    /* q counts units; turn it into exponent and fraction fields (a carry moves up by itself) */
+    uint32_t bits;
+    if (e < emin) bits = (uint32_t)q;                   /* subnormal, or exactly the smallest normal */
+    else bits = (uint32_t)(((uint64_t)(e + bias - 1) << keep) + q);   /* q includes the hidden one */
+    if (bits >= inf || e > emax) return (uint16_t)(sign | inf);       /* overflow to infinity */
+    return (uint16_t)(sign | bits);
+}
+
+uint16_t oracle_f64_to_bf16(double d) { return round_double_to_16(d, 7, -126, 127, 127); }
+uint16_t oracle_f64_to_f16(double d) { return round_double_to_16(d, 10, -14, 15, 15); }
+
+static uint16_t narrow16_from_double(int fmt, double d) { return fmt ? oracle_f64_to_f16(d) : oracle_f64_to_bf16(d); }
+
+/* Reference mode: the unrounded doubles.  x, g: uint16 [W][ld]; v: float [W][ld]. */
+int oracle_sgd_fused_mix16_f64(int fmt, const uint16_t *x_in, const float *v_in, const uint16_t *g,
+                               double *x_out, double *v_out, float lr, float mu, float wd,
+                               int64_t ld, int32_t W, int64_t P, int32_t S,
+                               const int64_t *seg_off, const int32_t *peers)
+{
+    (void)P;
+    double *xh = (double *)malloc(sizeof(double) * (size_t)W);
+    if (!xh) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t i = 0; i < W; ++i) {
+                int64_t e = i * ld + c;
+                double x = (double)widen16(fmt, x_in[e]);
+                double gp = (double)widen16(fmt, g[e]) + (double)wd * x;
+                double vn = (double)mu * (double)v_in[e] + gp;
+                v_out[e] = vn;
+                xh[i] = x - (double)lr * vn;
+            }
+            for (int32_t i = 0; i < W; ++i)
+                x_out[i * ld + c] = (xh[i] + xh[peers[(int64_t)s * W + i]]) * 0.5;
+        }
+    free(xh);
+    return 0;
+}
+
+/* The step as the 16-bit entry points return it: x' in the 16-bit format, v' in fp32, each
+ * rounded once from the reference's double. */
+int oracle_sgd_fused_mix16(int fmt, const uint16_t *x_in, const float *v_in, const uint16_t *g,
+                           uint16_t *x_out, float *v_out, float lr, float mu, float wd,
+                           int64_t ld, int32_t W, int64_t P, int32_t S,
+                           const int64_t *seg_off, const int32_t *peers)
+{
+    size_t n = (size_t)W * (size_t)ld;
+    double *x64 = (double *)calloc(n, sizeof(double)), *v64 = (double *)calloc(n, sizeof(double));
+    if (!x64 || !v64) { free(x64); free(v64); return -2; }
+    int rc = oracle_sgd_fused_mix16_f64(fmt, x_in, v_in, g, x64, v64, lr, mu, wd, ld, W, P, S, seg_off, peers);
+    for (int32_t s = 0; rc == 0 && s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c)
+            for (int32_t i = 0; i < W; ++i) {
+                x_out[i * ld + c] = narrow16_from_double(fmt, x64[i * ld + c]);
+                v_out[i * ld + c] = (float)v64[i * ld + c];
+            }
+    free(x64);
+    free(v64);
+    return rc;
+}
+
+/* Section 3.3 with gradients on 16-bit rows: g uint16 [W][ld], x uint16 [W][ld] (leader rows
+ * read, all rows written), v float [L][ld]. */
+int oracle_hier_sgd_fused_mix16_f64(int fmt, const uint16_t *x_in, const float *v_in, const uint16_t *g,
+                                    double *x_out, double *v_out, float lr, float mu, float wd,
+                                    int64_t ld, int32_t W, int64_t P, int32_t G, int32_t S,
+                                    const int64_t *seg_off, const int32_t *leader_peers)
+{
+    (void)P;
+    int32_t L = W / G;
+    double *h = (double *)malloc(sizeof(double) * (size_t)L);
+    if (!h) return -2;
+    for (int32_t s = 0; s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t q = 0; q < L; ++q) {
+                double gbar = 0.0;
+                for (int32_t j = 0; j < G; ++j)
+                    gbar += (double)widen16(fmt, g[((int64_t)q * G + j) * ld + c]);
+                gbar /= (double)G;
+                double xl = (double)widen16(fmt, x_in[(int64_t)q * G * ld + c]);
+                double gp = gbar + (double)wd * xl;
+                double vn = (double)mu * (double)v_in[(int64_t)q * ld + c] + gp;
+                v_out[(int64_t)q * ld + c] = vn;
+                h[q] = xl - (double)lr * vn;
+            }
+            for (int32_t q = 0; q < L; ++q) {
+                double y = h[q];
+                if (L > 1) y = (h[q] + h[leader_peers[(int64_t)s * L + q]]) * 0.5;
+                for (int32_t j = 0; j < G; ++j)
+                    x_out[((int64_t)q * G + j) * ld + c] = y;
+            }
+        }
+    free(h);
+    return 0;
+}
+
+int oracle_hier_sgd_fused_mix16(int fmt, const uint16_t *x_in, const float *v_in, const uint16_t *g,
+                                uint16_t *x_out, float *v_out, float lr, float mu, float wd,
+                                int64_t ld, int32_t W, int64_t P, int32_t G, int32_t S,
+                                const int64_t *seg_off, const int32_t *leader_peers)
+{
+    int32_t L = W / G;
+    size_t n = (size_t)W * (size_t)ld, nl = (size_t)L * (size_t)ld;
+    double *x64 = (double *)calloc(n, sizeof(double)), *v64 = (double *)calloc(nl, sizeof(double));
+    if (!x64 || !v64) { free(x64); free(v64); return -2; }
+    int rc = oracle_hier_sgd_fused_mix16_f64(fmt, x_in, v_in, g, x64, v64, lr, mu, wd, ld, W, P, G, S, seg_off, leader_peers);
+    for (int32_t s = 0; rc == 0 && s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c) {
+            for (int32_t i = 0; i < W; ++i) x_out[i * ld + c] = narrow16_from_double(fmt, x64[i * ld + c]);
+            for (int32_t q = 0; q < L; ++q) v_out[q * ld + c] = (float)v64[q * ld + c];
+        }
+    free(x64);
+    free(v64);
+    return rc;
 }
 
 /* ------------------------------------------------------------------------- */

@@ -23,7 +23,9 @@ __all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topo
            "gossip_mix", "hier_mix_f64", "hier_mix_f32", "sgd_fused_mix_f64",
            "sgd_fused_mix_f32", "pushsum_mix_f64", "pushsum_mix_f32",
            "hier_sgd_fused_mix_f64", "hier_sgd_fused_mix_f32", "gossip_mix_bf16", "f32_to_bf16",
-           "bf16_to_f32", "gossip_mix_f16", "f32_to_f16", "f16_to_f32", "hier_mix16_f64", "hier_mix16_f32"]
+           "bf16_to_f32", "gossip_mix_f16", "f32_to_f16", "f16_to_f32", "hier_mix16_f64", "hier_mix16_f32",
+           "f64_to_bf16", "f64_to_f16", "sgd_fused_mix16_f64", "sgd_fused_mix16",
+           "hier_sgd_fused_mix16_f64", "hier_sgd_fused_mix16"]
 
 
 def build_oracle(force: bool = False) -> str:
@@ -75,6 +77,13 @@ def _L():
                                                  i64, i32, i64, i32, vp, vp]
         for fn in (lib.oracle_hier_sgd_fused_mix_f64, lib.oracle_hier_sgd_fused_mix_f32):
             fn.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32, vp, vp]
+        for fn in (lib.oracle_f64_to_bf16, lib.oracle_f64_to_f16):
+            fn.restype = ctypes.c_uint16
+            fn.argtypes = [ctypes.c_double]
+        for fn in (lib.oracle_sgd_fused_mix16_f64, lib.oracle_sgd_fused_mix16):
+            fn.argtypes = [i32, vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, vp, vp]
+        for fn in (lib.oracle_hier_sgd_fused_mix16_f64, lib.oracle_hier_sgd_fused_mix16):
+            fn.argtypes = [i32, vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_pushsum_mix_f64.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
         lib.oracle_pushsum_mix_f32.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
         _lib = lib
@@ -327,3 +336,56 @@ def hier_mix16_f32(fmt, x, P, G, seg_off, leader_peers) -> np.ndarray:
     format: uint16 [W][ld]."""
     x = _mat(x, dtype=np.uint16)
     return _hier16(_L().oracle_hier_mix16_f32, fmt, x, x.copy(), P, G, seg_off, leader_peers)
+
+
+# ------------------------------------------------- optimizer steps on 16-bit rows
+def f64_to_bf16(a) -> np.ndarray:
+    """bfloat16 bit patterns of doubles, ONE rounding to nearest even straight from the double."""
+    a = np.asarray(a, dtype=np.float64)
+    fn = _L().oracle_f64_to_bf16
+    return np.array([fn(float(v)) for v in a.ravel()], dtype=np.uint16).reshape(a.shape)
+
+
+def f64_to_f16(a) -> np.ndarray:
+    a = np.asarray(a, dtype=np.float64)
+    fn = _L().oracle_f64_to_f16
+    return np.array([fn(float(v)) for v in a.ravel()], dtype=np.uint16).reshape(a.shape)
+
+
+def _fused16(fn, reference, fmt, x, v, g, lr, mu, wd, P, seg_off, peers, G=None):
+    x, g, v = _mat(x, dtype=np.uint16), _mat(g, dtype=np.uint16), _mat(v)
+    W, ld = x.shape
+    n = W if G is None else W // G
+    if G is not None and (G < 1 or W % G):
+        raise ValueError("G must divide W")
+    if g.shape != x.shape or v.shape != (n, ld):
+        raise ValueError("x, g: uint16 [W][ld]; v: float32 [W or W/G][ld]")
+    so = _seg(seg_off, P)
+    S = len(so) - 1
+    pe = _peers(peers, S, n) if n > 1 else None
+    widened = bf16_to_f32(x) if fmt == "bf16" else f16_to_f32(x)
+    xo = widened.astype(np.float64) if reference else x.copy()
+    vo = v.astype(np.float64) if reference else v.copy()
+    args = [_FMT[fmt], _p(x), _p(v), _p(g), _p(xo), _p(vo), lr, mu, wd, ld, W, P]
+    args += [S, _p(so), _p(pe)] if G is None else [G, S, _p(so), _p(pe)]
+    _check(fn(*args), "sgd_fused_mix16")
+    return xo, vo
+
+
+def sgd_fused_mix16_f64(fmt, x, v, g, lr, mu, wd, P, seg_off, peers):
+    """Momentum-SGD + mix on 16-bit parameter and gradient rows ("bf16" / "f16" bit patterns) with
+    fp32 momentum, in double, NOT rounded back: (float64 x', float64 v')."""
+    return _fused16(_L().oracle_sgd_fused_mix16_f64, True, fmt, x, v, g, lr, mu, wd, P, seg_off, peers)
+
+
+def sgd_fused_mix16(fmt, x, v, g, lr, mu, wd, P, seg_off, peers):
+    """The same with x' rounded once to the 16-bit format and v' once to fp32: (uint16, float32)."""
+    return _fused16(_L().oracle_sgd_fused_mix16, False, fmt, x, v, g, lr, mu, wd, P, seg_off, peers)
+
+
+def hier_sgd_fused_mix16_f64(fmt, x, v, g, lr, mu, wd, P, G, seg_off, leader_peers):
+    return _fused16(_L().oracle_hier_sgd_fused_mix16_f64, True, fmt, x, v, g, lr, mu, wd, P, seg_off, leader_peers, G)
+
+
+def hier_sgd_fused_mix16(fmt, x, v, g, lr, mu, wd, P, G, seg_off, leader_peers):
+    return _fused16(_L().oracle_hier_sgd_fused_mix16, False, fmt, x, v, g, lr, mu, wd, P, seg_off, leader_peers, G)
