@@ -31,6 +31,14 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 
 
+def dtype_of(kind, rows16) -> str:
+    """The type the path computes in: the mixing steps in fp32, the optimizer steps in fp64 registers."""
+    arith = "f64" if kind in ("fused", "hiersgd") else "f32"
+    if rows16:
+        return f"{arith} ({rows16} rows" + (", f32 momentum" if arith == "f64" else "") + " in HBM)"
+    return arith if arith == "f32" else "f64 (f32 rows in HBM)"
+
+
 def describe(wl, rows="fp32") -> str:
     s = f"{wl.name}: W={wl.W} P={wl.P} {rows} S={wl.S}"
     if wl.G > 1:
@@ -69,11 +77,15 @@ class Runner:
         self.tab_np = self.tab_host.numpy()
         self.tab_dev = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, device=dev)
         self.bytes_per_elem = 4 if rows16 else 8
+        dt16 = (torch.bfloat16 if rows16 == "bf16" else torch.float16) if rows16 else None
         if kind == "fused":
-            self.v = torch.zeros_like(self.x)
+            self.v = torch.zeros((wl.W, self.ld), device=dev)              # the momentum stays fp32
             self.v2 = self.v if in_place else torch.empty_like(self.v)
             self.g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
             self.bytes_per_elem = 20
+            if rows16:
+                self.g = self.g.to(dt16)
+                self.bytes_per_elem = 14                                   # read x, g (2 B) and v (4 B); write x, v
         if kind == "hiersgd":
             c4 = WL.WORKLOADS["C4"]            # optimizer constants and gradient scale of C4
             self.lr, self.mu, self.wd = c4.lr, c4.mu, c4.wd
@@ -81,6 +93,9 @@ class Runner:
             self.v = torch.zeros((wl.L, self.ld), device=dev)
             self.v2 = self.v if in_place else torch.empty_like(self.v)
             self.g = WL.gen_matrix_device(wl.W, wl.P, c4.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
+            if rows16:
+                self.g = self.g.to(dt16)
+                self.bytes_per_elem = 4 + 10.0 / wl.G
         if kind == "pushsum":
             self.w = [torch.ones(wl.W, device=dev), torch.zeros(wl.W, device=dev)]
         self.round = 0
@@ -106,12 +121,13 @@ class Runner:
         elif self.kind == "hier":
             cx.cx_hier_mix(self.x, self.y, wl.P, wl.G, self.so, tab)
         elif self.kind == "fused":
-            cx.cx_sgd_fused_mix(self.x, self.y, self.v, self.v2, self.g, wl.lr, wl.mu, wl.wd, wl.P,
-                                self.so, tab)
+            fused = {None: cx.cx_sgd_fused_mix, "bf16": cx.cx_sgd_fused_mix_bf16, "f16": cx.cx_sgd_fused_mix_f16}[self.rows16]
+            fused(self.x, self.y, self.v, self.v2, self.g, wl.lr, wl.mu, wl.wd, wl.P, self.so, tab)
             self.v, self.v2 = self.v2, self.v
         elif self.kind == "hiersgd":
-            cx.cx_hier_sgd_fused_mix(self.x, self.y, self.v, self.v2, self.g, self.lr, self.mu, self.wd,
-                                     wl.P, wl.G, self.so, tab)
+            hsgd = {None: cx.cx_hier_sgd_fused_mix, "bf16": cx.cx_hier_sgd_fused_mix_bf16,
+                    "f16": cx.cx_hier_sgd_fused_mix_f16}[self.rows16]
+            hsgd(self.x, self.y, self.v, self.v2, self.g, self.lr, self.mu, self.wd, wl.P, wl.G, self.so, tab)
             self.v, self.v2 = self.v2, self.v
         elif self.kind == "pushsum":
             hop = int((0 - int(self.tab_np[r, 0, 0])) % wl.W)
@@ -267,20 +283,20 @@ def main():
     if args.bf16 and args.f16:
         sys.exit("bench.py: --bf16 and --f16 exclude each other")
     rows16 = "bf16" if args.bf16 else "f16" if args.f16 else None
-    if rows16 and kind not in ("gossip", "hier"):
-        sys.exit("bench.py: --bf16 / --f16 are available for the gossip and hierarchical entry points only")
+    if rows16 and kind == "pushsum":
+        sys.exit("bench.py: --bf16 / --f16 are not available for the push-sum comparison")
     runner = Runner(wl, kind, args.steps + args.warmup, in_place=args.in_place, rows16=rows16)
     res = runner.run(args.steps, args.warmup)
     out = {
         "metric": "gossip-mix HBM GB/s and params-mixed/s per round (fraction of HBM peak), 1 GPU",
         "value": res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": f"{rows16} rows, f32 arithmetic" if rows16 else "f32",
+        "scaling": "weak", "vs_baseline": None, "dtype": dtype_of(kind, rows16),
         "data": "synthetic",
         "config": {"workload": describe(wl, rows16 or "fp32") if kind != "gossip" or wl.G == 1
                    else describe(wl, rows16 or "fp32") + " (flat gossip over all rows)",
                    "entry_point": {"fused": "cx_sgd_fused_mix", "hiersgd": "cx_hier_sgd_fused_mix"}.get(
-                       kind, f"cx_{kind}_mix" + ("_" + rows16 if rows16 else "")),
+                       kind, f"cx_{kind}_mix") + ("_" + rows16 if rows16 else ""),
                    "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
                    "buffers": "in place" if args.in_place else "ping-pong (x_in -> x_out, swapped every round)",
                    "step": "cx_topology_gen(1 round) + table upload + one mixing launch",

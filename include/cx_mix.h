@@ -287,6 +287,36 @@ int cx_hier_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W
                     const int32_t *leader_peers_dev, uint32_t flags, void *stream);
 
 /* ------------------------------------------------------------------------------------
+ * cx_sgd_fused_mix_bf16 / _f16 and cx_hier_sgd_fused_mix_bf16 / _f16 -- the two optimizer steps on
+ * mixed-precision state (Section 4.1 / Table 1: the paper trains in mixed precision): parameters x and
+ * gradients g are uint16 [W][ld] of bfloat16 / binary16 bit patterns, the momentum v stays float32
+ * ([W][ld], or [L][ld] in the hierarchical step), all with the same ld, ld % 8 == 0.
+ * Every input is widened exactly and the step runs in fp64 exactly as in cx_sgd_fused_mix /
+ * cx_hier_sgd_fused_mix; v' is rounded once to fp32 and x' ONCE to the 16-bit format (nearest even,
+ * straight from the fp64 value: not through fp32, which could land on the wrong side of a tie).
+ * Bytes per worker-parameter: 14 (flat: read x, g, v; write x, v) and 4 + 10/G (hierarchical).
+ * x and v are updated either both in place or both out of place (CX_ERR_ALIAS otherwise, and
+ * for any other overlap between x, v and g).  Hierarchical group sizes: 1, 2, 4, 8.
+ * Everything else as cx_sgd_fused_mix and cx_hier_sgd_fused_mix.
+ */
+int cx_sgd_fused_mix_bf16(const uint16_t *x_in, uint16_t *x_out, const float *v_in, float *v_out,
+                          const uint16_t *g, float lr, float mu, float wd, int64_t ld, int32_t W,
+                          int64_t P, int32_t S, const int64_t *seg_off_dev, const int32_t *peers_dev,
+                          uint32_t flags, void *stream);
+int cx_sgd_fused_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float *v_in, float *v_out,
+                         const uint16_t *g, float lr, float mu, float wd, int64_t ld, int32_t W,
+                         int64_t P, int32_t S, const int64_t *seg_off_dev, const int32_t *peers_dev,
+                         uint32_t flags, void *stream);
+int cx_hier_sgd_fused_mix_bf16(const uint16_t *x_in, uint16_t *x_out, const float *v_in, float *v_out,
+                               const uint16_t *g, float lr, float mu, float wd, int64_t ld, int32_t W,
+                               int64_t P, int32_t G, int32_t S, const int64_t *seg_off_dev,
+                               const int32_t *leader_peers_dev, uint32_t flags, void *stream);
+int cx_hier_sgd_fused_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float *v_in, float *v_out,
+                              const uint16_t *g, float lr, float mu, float wd, int64_t ld, int32_t W,
+                              int64_t P, int32_t G, int32_t S, const int64_t *seg_off_dev,
+                              const int32_t *leader_peers_dev, uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
  * Measurement helpers (not part of the method).
  * cx_copy_baseline: dst[i] = src[i] for n floats (n % 4 == 0, 16-byte aligned) with the
  * same load/store instructions as the mixing kernels; the practical HBM ceiling and the

@@ -499,6 +499,207 @@ struct Row16Op {
 using Bf16Op = Row16Op<false>;
 using Fp16Op = Row16Op<true>;
 
+// ---------------------------------------------------------------------------------
+// The optimizer operators on 16-bit rows: parameters and gradients are 16-bit (8 columns per
+// 16-byte slice), the momentum stays fp32 (the same 8 columns are two 16-byte registers).
+// Everything is widened exactly, the chain runs in fp64 as in FusedOp, v' is rounded once to
+// fp32 and x' ONCE to the 16-bit format: the double is first narrowed to fp32 with rounding to
+// odd (the discarded bits survive as a sticky last bit), which makes the hardware's
+// round-to-nearest-even conversion to 16 bits equal to one rounding of the double itself.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ float to_f32_round_to_odd(double d)
+{
+    const float f = static_cast<float>(d);                 // nearest even
+    const double back = static_cast<double>(f);
+    unsigned bits = __float_as_uint(f);
+    if (back != d && d == d) {                             // inexact (and not a NaN)
+        if (__builtin_fabs(back) > __builtin_fabs(d)) bits -= 1;   // step back to the truncated value
+        bits |= 1u;                                        // and remember that something was cut off
+    }
+    return __uint_as_float(bits);
+}
+
+// fp32 companion rows of 16-bit rows: slice u = 8 floats at p + u*512, two registers.
+template <int U, bool FULL, bool NT>
+__device__ __forceinline__ void tile_load8(const float *p, const unsigned (&mask)[U], Tile<2 * U> &t)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const float *q = p + u * (kWave * 8) + 4 * hh;
+            if constexpr (FULL) {
+                const f4 *q4 = reinterpret_cast<const f4 *>(q);
+                t.v[2 * u + hh] = NT ? __builtin_nontemporal_load(q4) : *q4;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) t.v[2 * u + hh][e] = ((mask[u] >> (4 * hh + e)) & 1u) ? q[e] : 0.0f;
+            }
+        }
+}
+
+template <int U, bool FULL, bool NT>
+__device__ __forceinline__ void tile_store8(float *p, const unsigned (&mask)[U], const Tile<2 * U> &t)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            float *q = p + u * (kWave * 8) + 4 * hh;
+            if constexpr (FULL) {
+                f4 *q4 = reinterpret_cast<f4 *>(q);
+                if (NT) __builtin_nontemporal_store(t.v[2 * u + hh], q4); else *q4 = t.v[2 * u + hh];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((mask[u] >> (4 * hh + e)) & 1u) q[e] = t.v[2 * u + hh][e];
+            }
+        }
+}
+
+// columns 4*hh .. 4*hh+3 of a packed 16-bit slice, widened exactly to doubles
+template <bool IEEE_HALF>
+__device__ __forceinline__ d4 widen16_half(const f4 &packed, int hh)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    const u4 w = __builtin_bit_cast(u4, packed);
+    d4 out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const unsigned pair = hh == 0 ? w[e >> 1] : w[2 + (e >> 1)];
+        const unsigned h = (pair >> (16 * (e & 1))) & 0xffffu;
+        out[e] = static_cast<double>(IEEE_HALF ? f16_bits_to_float(h) : bf16_bits_to_float(h));
+    }
+    return out;
+}
+
+// eight doubles -> one packed 16-bit slice, each rounded once (nearest even)
+template <bool IEEE_HALF>
+__device__ __forceinline__ f4 narrow16_once(const d4 &lo, const d4 &hi)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    u4 w;
+#pragma unroll
+    for (int pair = 0; pair < 4; ++pair) {
+        const d4 &src = pair < 2 ? lo : hi;
+        const f2 two = {to_f32_round_to_odd(src[2 * (pair & 1)]), to_f32_round_to_odd(src[2 * (pair & 1) + 1])};
+        if constexpr (IEEE_HALF) w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, h2));
+        else w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
+    }
+    return __builtin_bit_cast(f4, w);
+}
+
+// cx_sgd_fused_mix_bf16 / _f16: FusedOp with 16-bit x and g rows and fp32 momentum rows.
+template <bool IEEE_HALF>
+struct Fused16Op {
+    static constexpr int kElems = 8;                       // 16-bit columns per 16-byte slice
+    template <int U> using Work = WideTile<2 * U>;         // the updated row, 8 doubles per slice
+    static constexpr int kRawPerSlice = 4;                 // x, g: one register each; v: two
+    static constexpr GatherShape kGather{1, 8, 192, 0};
+    static constexpr WalkShape kWalk{1, 2, 4, 2};
+    static constexpr int kMaxU = 1;
+    template <int U> struct Raw { Tile<U> x, g; Tile<2 * U> v; };
+    const uint16_t *xin;
+    uint16_t *xout;
+    const float *vin;
+    float *vout;
+    const uint16_t *g;
+    int64_t ld;
+    SgdStep sgd;
+
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
+    {
+        const int64_t o = static_cast<int64_t>(row) * ld + off;
+        tile_load16<U, FULL, NT>(xin + o, mask, raw.x);
+        tile_load8<U, FULL, NT>(vin + o, mask, raw.v);
+        tile_load16<U, FULL, NT>(g + o, mask, raw.g);
+    }
+    template <int U, bool FULL, bool NT, bool COMMIT = true>
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
+    {
+        Tile<2 * U> v32;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                d4 v = widen(raw.v.v[2 * u + hh]);
+                t.v[2 * u + hh] = sgd.apply(widen16_half<IEEE_HALF>(raw.x.v[u], hh), v, widen16_half<IEEE_HALF>(raw.g.v[u], hh));
+                v32.v[2 * u + hh] = narrow(v);
+            }
+        if constexpr (COMMIT) tile_store8<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
+    }
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
+    {
+        Tile<U> packed;
+#pragma unroll
+        for (int u = 0; u < U; ++u) packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
+        tile_store16<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
+    }
+};
+
+// cx_hier_sgd_fused_mix_bf16 / _f16: HierFusedOp with 16-bit x and g rows, fp32 leader momentum.
+template <bool IEEE_HALF, int G>
+struct HierFused16Op {
+    static constexpr int kElems = 8;
+    template <int U> using Work = WideTile<2 * U>;
+    static constexpr int kRawPerSlice = G + 3;             // G gradient rows, x, and two registers of v
+    static constexpr GatherShape kGather =
+        G == 1 ? GatherShape{1, 8, 192, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
+    static constexpr WalkShape kWalk{1, 2, 2, 2};
+    static constexpr int kMaxU = 1;
+    template <int U> struct Raw { Tile<U> g[G], x; Tile<2 * U> v; };
+    const uint16_t *xin;
+    uint16_t *xout;
+    const float *vin;     // [L][ld]
+    float *vout;          // [L][ld]
+    const uint16_t *g;    // [W][ld]
+    int64_t ld;
+    SgdStep sgd;
+
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
+    {
+        const int64_t lead = static_cast<int64_t>(row) * G * ld + off;
+#pragma unroll
+        for (int j = 0; j < G; ++j) tile_load16<U, FULL, NT>(g + lead + j * ld, mask, raw.g[j]);
+        tile_load16<U, FULL, NT>(xin + lead, mask, raw.x);
+        tile_load8<U, FULL, NT>(vin + static_cast<int64_t>(row) * ld + off, mask, raw.v);
+    }
+    template <int U, bool FULL, bool NT, bool COMMIT = true>
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
+    {
+        Tile<2 * U> v32;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                d4 gsum = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int j = 0; j < G; ++j) gsum = gsum + widen16_half<IEEE_HALF>(raw.g[j].v[u], hh);
+                const d4 gbar = gsum / static_cast<double>(G);
+                d4 v = widen(raw.v.v[2 * u + hh]);
+                t.v[2 * u + hh] = sgd.apply(widen16_half<IEEE_HALF>(raw.x.v[u], hh), v, gbar);
+                v32.v[2 * u + hh] = narrow(v);
+            }
+        if constexpr (COMMIT) tile_store8<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
+    }
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
+    {
+        Tile<U> packed;
+#pragma unroll
+        for (int u = 0; u < U; ++u) packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
+        uint16_t *p = xout + static_cast<int64_t>(row) * G * ld + off;
+#pragma unroll
+        for (int j = 0; j < G; ++j) tile_store16<U, FULL, NT>(p + j * ld, mask, packed);
+    }
+};
+
 // Push-sum: plain rows, optional de-biased copy z = x' / w'.
 struct PushOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice

@@ -29,6 +29,7 @@ TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE, TUNE_ORDERED, TUNE
 EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_segments",
            "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",
            "cx_sgd_fused_mix", "cx_hier_sgd_fused_mix", "cx_gossip_mix_noalloc", "cx_gossip_mix_bf16", "cx_gossip_mix_f16", "cx_hier_mix_bf16", "cx_hier_mix_f16",
+           "cx_sgd_fused_mix_bf16", "cx_sgd_fused_mix_f16", "cx_hier_sgd_fused_mix_bf16", "cx_hier_sgd_fused_mix_f16",
            "cx_copy_baseline", "cx_set_tuning",
            "cx_get_tuning"]
 
@@ -50,6 +51,13 @@ def lib() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with "
                           "`python -m paper_2012_15198_amd.build` (hipcc, gfx950)")
+    # torch first: its wheel carries its own HIP runtime, and the library must bind to the SAME runtime
+    # instance that owns the tensors and streams it is handed (loaded the other way round, the two end
+    # up on different instances and every launch on a torch stream fails with CX_ERR_HIP)
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(LIB_PATH)
     i32, i64, u32, u64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_uint64
     f32, vp = ctypes.c_float, ctypes.c_void_p
@@ -72,6 +80,10 @@ def lib() -> ctypes.CDLL:
                                    vp, vp, u32, vp]
     L.cx_hier_sgd_fused_mix.argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32,
                                         vp, vp, u32, vp]
+    for name in ("cx_sgd_fused_mix_bf16", "cx_sgd_fused_mix_f16"):
+        getattr(L, name).argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, vp, vp, u32, vp]
+    for name in ("cx_hier_sgd_fused_mix_bf16", "cx_hier_sgd_fused_mix_f16"):
+        getattr(L, name).argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32, vp, vp, u32, vp]
     L.cx_copy_baseline.argtypes = [vp, vp, i64, vp]
     L.cx_set_tuning.argtypes = [i32, i32]
     L.cx_get_tuning.argtypes = [i32]
@@ -315,6 +327,54 @@ def cx_hier_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd:
     _ok("cx_hier_sgd_fused_mix", lib().cx_hier_sgd_fused_mix(
         _dptr(x_in), _dptr(x_out), _dptr(v_in), _dptr(v_out), _dptr(g), lr, mu, wd, ld, W, P, G, S,
         _dptr(seg_off_dev), _dptr(leader_peers_dev), flags, _stream(stream)))
+
+
+def _fused16(name, x_in, x_out, v_in, v_out, g, lr, mu, wd, P, seg_off_dev, peers_dev, flags, stream):
+    W, ld = _shape(x_in, 2)
+    for nm, t, size in (("x_out", x_out, 2), ("g", g, 2), ("v_in", v_in, 4), ("v_out", v_out, 4)):
+        _matrix(nm, t, W, ld, size)
+    S = _tables(x_in, P, seg_off_dev, peers_dev, W)
+    _same_device(x_in, x_out, v_in, v_out, g, seg_off_dev, peers_dev)
+    _ok(name, getattr(lib(), name)(_dptr(x_in), _dptr(x_out), _dptr(v_in), _dptr(v_out), _dptr(g), lr, mu, wd,
+                                   ld, W, P, S, _dptr(seg_off_dev), _dptr(peers_dev), flags, _stream(stream)))
+
+
+def cx_sgd_fused_mix_bf16(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: float, P: int,
+                          seg_off_dev, peers_dev, flags: int = 0, stream=None):
+    """x, g: torch.bfloat16 (or int16 bit patterns) [W][ld]; v: float32 [W][ld], same ld."""
+    _fused16("cx_sgd_fused_mix_bf16", x_in, x_out, v_in, v_out, g, lr, mu, wd, P, seg_off_dev, peers_dev, flags, stream)
+
+
+def cx_sgd_fused_mix_f16(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: float, P: int,
+                         seg_off_dev, peers_dev, flags: int = 0, stream=None):
+    """x, g: torch.float16 (or int16 bit patterns) [W][ld]; v: float32 [W][ld], same ld."""
+    _fused16("cx_sgd_fused_mix_f16", x_in, x_out, v_in, v_out, g, lr, mu, wd, P, seg_off_dev, peers_dev, flags, stream)
+
+
+def _hier_fused16(name, x_in, x_out, v_in, v_out, g, lr, mu, wd, P, G, seg_off_dev, leader_peers_dev, flags, stream):
+    W, ld = _shape(x_in, 2)
+    L = _leaders(W, G)
+    for nm, t, rows, size in (("x_out", x_out, W, 2), ("g", g, W, 2), ("v_in", v_in, L, 4), ("v_out", v_out, L, 4)):
+        _matrix(nm, t, rows, ld, size)
+    S = _tables(x_in, P, seg_off_dev, leader_peers_dev, L)
+    _same_device(x_in, x_out, v_in, v_out, g, seg_off_dev, leader_peers_dev)
+    _ok(name, getattr(lib(), name)(_dptr(x_in), _dptr(x_out), _dptr(v_in), _dptr(v_out), _dptr(g), lr, mu, wd,
+                                   ld, W, P, G, S, _dptr(seg_off_dev), _dptr(leader_peers_dev), flags,
+                                   _stream(stream)))
+
+
+def cx_hier_sgd_fused_mix_bf16(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: float, P: int, G: int,
+                               seg_off_dev, leader_peers_dev, flags: int = 0, stream=None):
+    """x, g: bfloat16 [W][ld]; v: float32 [W/G][ld], same ld."""
+    _hier_fused16("cx_hier_sgd_fused_mix_bf16", x_in, x_out, v_in, v_out, g, lr, mu, wd, P, G, seg_off_dev,
+                  leader_peers_dev, flags, stream)
+
+
+def cx_hier_sgd_fused_mix_f16(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: float, P: int, G: int,
+                              seg_off_dev, leader_peers_dev, flags: int = 0, stream=None):
+    """x, g: float16 [W][ld]; v: float32 [W/G][ld], same ld."""
+    _hier_fused16("cx_hier_sgd_fused_mix_f16", x_in, x_out, v_in, v_out, g, lr, mu, wd, P, G, seg_off_dev,
+                  leader_peers_dev, flags, stream)
 
 
 def cx_copy_baseline(src, dst, stream=None):

@@ -253,6 +253,66 @@ def test_c3_shape_hierarchical_gradient_step_sampled_all_rounds():
     free(x, x2, v, v2, g)
 
 
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_c4_fused_sgd_on_16bit_rows_sampled_all_rounds(fmt):
+    """C4's fused step with bfloat16 / binary16 parameters and gradients and fp32 momentum."""
+    wl = WL.WORKLOADS["C4"]
+    so = WL.equal_seg_off(wl.P, wl.S)
+    ld = padded(wl.P)
+    dt = torch.bfloat16 if fmt == "bf16" else torch.float16
+    fused = cx.cx_sgd_fused_mix_bf16 if fmt == "bf16" else cx.cx_sgd_fused_mix_f16
+    tabs = cx.cx_topology_gen(wl.seed, wl.W, wl.S, 0, wl.rounds)
+    x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld).to(dt)
+    g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, ld=ld, stream=2).to(dt)
+    v = torch.zeros((wl.W, ld), device=x.device)
+    x2, v2 = torch.empty_like(x), torch.empty_like(v)
+    cols, sso, cold = sample(wl, so)
+    grab16 = lambda t: host(t.view(torch.int16).index_select(1, cold)).view(np.uint16)
+    sx, sv, sg = grab16(x), take(v, cold), grab16(g)
+    sod = dev(so)
+    n = len(cols)
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        if r % 2 == 0:
+            fused(x, x2, v, v2, g, wl.lr, wl.mu, wl.wd, wl.P, sod, t)
+            x, x2, v, v2 = x2, x, v2, v
+        else:
+            fused(x, x, v, v, g, wl.lr, wl.mu, wl.wd, wl.P, sod, t)
+        sx, sv = O.sgd_fused_mix16(fmt, sx, sv, sg, wl.lr, wl.mu, wl.wd, n, sso, tabs[r])
+        assert (grab16(x) == sx).all() and same_bits(take(v, cold), sv), r
+    free(x, x2, v, v2, g)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_c3_shape_hierarchical_gradient_step_on_16bit_rows_sampled_all_rounds(fmt):
+    wl, c4 = WL.WORKLOADS["C3"], WL.WORKLOADS["C4"]
+    lr, mu, wd = c4.lr, c4.mu, c4.wd
+    so = WL.seg_off_for(wl)
+    ld = padded(wl.P)
+    dt = torch.bfloat16 if fmt == "bf16" else torch.float16
+    hsgd = cx.cx_hier_sgd_fused_mix_bf16 if fmt == "bf16" else cx.cx_hier_sgd_fused_mix_f16
+    tabs = cx.cx_topology_gen(wl.seed, wl.L, wl.S, 0, wl.rounds)
+    x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld).to(dt)
+    g = WL.gen_matrix_device(wl.W, wl.P, c4.grad_sigma, wl.seed, ld=ld, stream=2).to(dt)
+    v = torch.zeros((wl.L, ld), device=x.device)
+    x2, v2 = torch.empty_like(x), torch.empty_like(v)
+    cols, sso, cold = sample(wl, so)
+    grab16 = lambda t: host(t.view(torch.int16).index_select(1, cold)).view(np.uint16)
+    sx, sv, sg = grab16(x), take(v, cold), grab16(g)
+    sod = dev(so)
+    n = len(cols)
+    for r in range(wl.rounds):
+        t = dev(tabs[r])
+        if r % 2 == 0:
+            hsgd(x, x2, v, v2, g, lr, mu, wd, wl.P, wl.G, sod, t)
+            x, x2, v, v2 = x2, x, v2, v
+        else:
+            hsgd(x, x, v, v, g, lr, mu, wd, wl.P, wl.G, sod, t)
+        sx, sv = O.hier_sgd_fused_mix16(fmt, sx, sv, sg, lr, mu, wd, n, wl.G, sso, tabs[r])
+        assert (grab16(x) == sx).all() and same_bits(take(v, cold), sv), r
+    free(x, x2, v, v2, g)
+
+
 def test_c4_pushsum_sampled_all_rounds():
     wl = WL.WORKLOADS["C4"]
     ld = padded(wl.P)

@@ -1,0 +1,197 @@
+"""GPU parity of the optimizer entry points on 16-bit rows (cx_sgd_fused_mix_bf16 / _f16,
+cx_hier_sgd_fused_mix_bf16 / _f16) against the oracle, through the C ABI: x' bit for bit in the
+16-bit format (any NaN equals any NaN), v' bit for bit in fp32."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2012_15198_amd import cxmix as cx
+from paper_2012_15198_amd import workloads as WL
+from gpu_util import ALL_TUNINGS, Tuning, dev, host, same_bits
+
+pytestmark = pytest.mark.gpu
+
+NARROW = {"bf16": O.f32_to_bf16, "f16": O.f32_to_f16}
+FLAT = {"bf16": cx.cx_sgd_fused_mix_bf16, "f16": cx.cx_sgd_fused_mix_f16}
+HIER = {"bf16": cx.cx_hier_sgd_fused_mix_bf16, "f16": cx.cx_hier_sgd_fused_mix_f16}
+NAN = {"bf16": (0x7F80, 0x007F), "f16": (0x7C00, 0x03FF)}
+LR, MU, WD = 0.1, 0.9, 1e-4
+
+
+def same16(fmt, a, b):
+    e, m = NAN[fmt]
+    isnan = lambda h: ((h & e) == e) & ((h & m) != 0)
+    a, b = np.asarray(a, dtype=np.uint16), np.asarray(b, dtype=np.uint16)
+    return bool(((a == b) | (isnan(a) & isnan(b))).all())
+
+
+def d16(a):
+    return dev(np.ascontiguousarray(a).view(np.int16))
+
+
+def h16(t):
+    return host(t).view(np.uint16)
+
+
+def inputs(fmt, W, P, ld, seed, vrows=None, vscale=0.02):
+    x = NARROW[fmt](WL.gen_matrix(W, P, 0.05, seed=seed, ld=ld))
+    g = NARROW[fmt](WL.gen_matrix(W, P, 0.01, seed=seed, ld=ld, stream=2))
+    v = WL.gen_matrix(vrows or W, P, vscale, seed=seed, ld=ld, stream=1)
+    return x, v, g
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+@pytest.mark.parametrize("W,P,ld,S", [(2, 1, 8, 1), (2, 13, 16, 2), (3, 2048, 2048, 1), (8, 9001, 9008, 4),
+                                      (5, 8195, 8320, 7), (33, 5003, 5008, 8)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_fused16_bit_exact(fmt, W, P, ld, S, inplace):
+    x, v, g = inputs(fmt, W, P, ld, seed=W * 5 + P, vscale=2.0 if W == 8 else 0.02)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(91, W, S, 0, 1)[0]
+    wx, wv = O.sgd_fused_mix16(fmt, x, v, g, LR, MU, WD, P, so, pe)
+    xd, vd, gd = d16(x), dev(v), d16(g)
+    xo, vo = (xd, vd) if inplace else (xd.clone(), vd.clone())
+    FLAT[fmt](xd, xo, vd, vo, gd, LR, MU, WD, P, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    assert same16(fmt, h16(xo), wx) and same_bits(host(vo), wv)
+    assert (h16(gd) == g).all()
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_fused16_every_bit_pattern_as_parameter_and_as_gradient(fmt):
+    """Row 0 runs through all 65,536 patterns (infinities, NaNs, subnormals, the largest values) as x
+    and, reversed, as g; the other rows hold random patterns and ordinary values."""
+    W, P, S = 4, 65536, 3
+    rng = np.random.default_rng(92)
+    x = rng.integers(0, 65536, size=(W, P)).astype(np.uint16)
+    g = NARROW[fmt](WL.gen_matrix(W, P, 0.01, seed=92, stream=2))
+    x[0] = np.arange(65536, dtype=np.uint16)
+    g[1] = np.arange(65536, dtype=np.uint16)[::-1]
+    x[2] = NARROW[fmt](WL.gen_matrix(1, P, 0.05, seed=93))[0]
+    v = WL.gen_matrix(W, P, 0.02, seed=92, stream=1)
+    so = WL.equal_seg_off(P, S)
+    pe = np.array([[1, 0, 3, 2], [2, 3, 0, 1], [3, 2, 1, 0]], dtype=np.int32)
+    with np.errstate(all="ignore"):
+        wx, wv = O.sgd_fused_mix16(fmt, x, v, g, LR, MU, WD, P, so, pe)
+    for inplace in (False, True):
+        xd, vd = d16(x), dev(v)
+        xo, vo = (xd, vd) if inplace else (xd.clone(), vd.clone())
+        FLAT[fmt](xd, xo, vd, vo, d16(g), LR, MU, WD, P, dev(so), dev(pe))
+        torch.cuda.synchronize()
+        assert same16(fmt, h16(xo), wx), inplace
+        assert same_bits(host(vo), wv), inplace
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_fused16_results_next_to_a_tie_are_rounded_once(fmt):
+    """Columns whose exact result lies 2^-31 beside the midpoint of two 16-bit values (the oracle's
+    hand case, tiled over a row with both signs): rounding through fp32 would return the other value."""
+    keep = 7 if fmt == "bf16" else 10
+    P = 4096
+    scale = np.ldexp(1.0, np.arange(P) % 12 - 6) * np.where(np.arange(P) % 2, -1.0, 1.0)   # exact powers of two
+    x = NARROW[fmt](np.stack([scale, scale * (1.0 + 2.0 ** -keep)]).astype(np.float32))
+    g = NARROW[fmt](np.stack([-scale * 2.0 ** -10, 0.0 * scale]).astype(np.float32))
+    v = np.zeros((2, P), dtype=np.float32)
+    lr = 2.0 ** -20
+    so, pe = np.array([0, P], dtype=np.int64), np.array([[1, 0]], dtype=np.int32)
+    wx, wv = O.sgd_fused_mix16(fmt, x, v, g, lr, 0.0, 0.0, P, so, pe)
+    x64, _ = O.sgd_fused_mix16_f64(fmt, x, v, g, lr, 0.0, 0.0, P, so, pe)
+    assert (NARROW[fmt](x64.astype(np.float32)) != wx).all()        # the trap is set in every column
+    xd, vd = d16(x), dev(v)
+    xo, vo = xd.clone(), vd.clone()
+    FLAT[fmt](xd, xo, vd, vo, d16(g), lr, 0.0, 0.0, P, dev(so), dev(pe))
+    FLAT[fmt](xd, xd, vd, vd, d16(g), lr, 0.0, 0.0, P, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    assert (h16(xo) == wx).all() and (h16(xd) == wx).all() and same_bits(host(vo), wv)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+@pytest.mark.parametrize("tuning", ALL_TUNINGS)
+def test_fused16_rounds_under_every_launch_shape(fmt, tuning):
+    W, P, ld, S, R = 10, 12345, 12352, 6, 3
+    x, v, _ = inputs(fmt, W, P, ld, seed=94)
+    v[:] = 0
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(94, W, S, 0, R)
+    gs = [NARROW[fmt](WL.gen_matrix(W, P, 0.01, seed=94, ld=ld, stream=10 + r)) for r in range(R)]
+    wx, wv = x, v
+    for r in range(R):
+        wx, wv = O.sgd_fused_mix16(fmt, wx, wv, gs[r], LR, MU, WD, P, so, tabs[r])
+    with Tuning(*tuning):
+        a, av = d16(x), dev(v)
+        y0, y1, u0, u1 = d16(x), d16(x), dev(v), dev(v)
+        for r in range(R):
+            gd = d16(gs[r])
+            FLAT[fmt](a, a, av, av, gd, LR, MU, WD, P, dev(so), dev(tabs[r]))
+            FLAT[fmt](y0, y1, u0, u1, gd, LR, MU, WD, P, dev(so), dev(tabs[r]))
+            y0, y1, u0, u1 = y1, y0, u1, u0
+        torch.cuda.synchronize()
+    assert same16(fmt, h16(a), wx) and same_bits(host(av), wv)
+    assert same16(fmt, h16(y0), wx) and same_bits(host(u0), wv)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+@pytest.mark.parametrize("W,G,P,ld,S", [(2, 2, 5, 8, 1), (4, 2, 13, 16, 2), (8, 1, 3001, 3008, 3), (8, 4, 9001, 9008, 4),
+                                        (64, 8, 4099, 4104, 16), (16, 8, 8195, 8320, 5), (8, 8, 2100, 2104, 3)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_hier_fused16_bit_exact(fmt, W, G, P, ld, S, inplace):
+    L = W // G
+    x, v, g = inputs(fmt, W, P, ld, seed=W + G + P, vrows=L)
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(95, L, S, 0, 1)[0] if L > 1 else None
+    wx, wv = O.hier_sgd_fused_mix16(fmt, x, v, g, LR, MU, WD, P, G, so, pe)
+    xd, vd, gd = d16(x), dev(v), d16(g)
+    xo, vo = (xd, vd) if inplace else (xd.clone(), vd.clone())
+    HIER[fmt](xd, xo, vd, vo, gd, LR, MU, WD, P, G, dev(so), dev(pe) if L > 1 else None)
+    torch.cuda.synchronize()
+    assert same16(fmt, h16(xo), wx) and same_bits(host(vo), wv)
+    assert (h16(gd) == g).all()
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+@pytest.mark.parametrize("tuning", ALL_TUNINGS)
+def test_hier_fused16_rounds_under_every_launch_shape(fmt, tuning):
+    W, G, P, ld, S, R = 32, 8, 6007, 6008, 5, 3
+    L = W // G
+    x, v, _ = inputs(fmt, W, P, ld, seed=96, vrows=L)
+    v[:] = 0
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(96, L, S, 0, R)
+    gs = [NARROW[fmt](WL.gen_matrix(W, P, 0.01, seed=96, ld=ld, stream=10 + r)) for r in range(R)]
+    wx, wv = x, v
+    for r in range(R):
+        wx, wv = O.hier_sgd_fused_mix16(fmt, wx, wv, gs[r], LR, MU, WD, P, G, so, tabs[r])
+    with Tuning(*tuning):
+        a, av = d16(x), dev(v)
+        y0, y1, u0, u1 = d16(x), d16(x), dev(v), dev(v)
+        for r in range(R):
+            gd = d16(gs[r])
+            HIER[fmt](a, a, av, av, gd, LR, MU, WD, P, G, dev(so), dev(tabs[r]))
+            HIER[fmt](y0, y1, u0, u1, gd, LR, MU, WD, P, G, dev(so), dev(tabs[r]))
+            y0, y1, u0, u1 = y1, y0, u1, u0
+        torch.cuda.synchronize()
+    assert same16(fmt, h16(a), wx) and same_bits(host(av), wv)
+    assert same16(fmt, h16(y0), wx) and same_bits(host(u0), wv)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_hier_fused16_every_gradient_pattern(fmt):
+    W, G, P, S = 8, 4, 65536, 2
+    rng = np.random.default_rng(97)
+    x = NARROW[fmt](WL.gen_matrix(W, P, 0.05, seed=97))
+    g = NARROW[fmt](WL.gen_matrix(W, P, 0.01, seed=97, stream=2))
+    g[1] = np.arange(65536, dtype=np.uint16)
+    x[4] = np.arange(65536, dtype=np.uint16)[::-1]
+    v = WL.gen_matrix(W // G, P, 0.02, seed=97, stream=1)
+    so = WL.equal_seg_off(P, S)
+    pe = np.array([[1, 0], [1, 0]], dtype=np.int32)
+    with np.errstate(all="ignore"):
+        wx, wv = O.hier_sgd_fused_mix16(fmt, x, v, g, LR, MU, WD, P, G, so, pe)
+    xd, vd = d16(x), dev(v)
+    xo, vo = xd.clone(), vd.clone()
+    HIER[fmt](xd, xo, vd, vo, d16(g), LR, MU, WD, P, G, dev(so), dev(pe))
+    HIER[fmt](xd, xd, vd, vd, d16(g), LR, MU, WD, P, G, dev(so), dev(pe))
+    torch.cuda.synchronize()
+    assert same16(fmt, h16(xo), wx) and same_bits(host(vo), wv)
+    assert same16(fmt, h16(xd), wx) and same_bits(host(vd), wv)

@@ -192,6 +192,26 @@ def test_mix_calls_reject_bad_arguments_on_the_host():
         assert hier16(ld=60, P=60) == -5 and hier16(x_out=A + 32) == -6 and hier16(flags=4) == -8
         assert hier16(G=16, W=32) == -8
 
+    def fused16(fn, hier=False, v_in=C, v_out=C, g=D, x_out=A, G=2, pe=T2, **kw):
+        a = {**ok, **kw}
+        if hier:
+            return fn(a["x_in"], x_out, v_in, v_out, g, 0.1, 0.9, 1e-4, a["ld"], a["W"], a["P"], G, a["S"], a["so"], pe,
+                      a["flags"], a["st"])
+        return fn(a["x_in"], x_out, v_in, v_out, g, 0.1, 0.9, 1e-4, a["ld"], a["W"], a["P"], a["S"], a["so"], a["pe"],
+                  a["flags"], a["st"])
+
+    for fn, hier in ((L.cx_sgd_fused_mix_bf16, False), (L.cx_sgd_fused_mix_f16, False),
+                     (L.cx_hier_sgd_fused_mix_bf16, True), (L.cx_hier_sgd_fused_mix_f16, True)):
+        assert fused16(fn, hier, g=None) == -1 and fused16(fn, hier, v_in=None) == -1 and fused16(fn, hier, x_in=None) == -1
+        assert fused16(fn, hier, ld=60, P=60) == -5 and fused16(fn, hier, g=D + 4) == -5 and fused16(fn, hier, ld=56) == -2
+        assert fused16(fn, hier, x_out=B) == -6                # x out of place, v in place
+        assert fused16(fn, hier, v_out=E) == -6                # v out of place, x in place
+        assert fused16(fn, hier, v_in=A, v_out=A) == -6 and fused16(fn, hier, g=C) == -6
+        assert fused16(fn, hier, flags=2) == -8
+    assert fused16(L.cx_sgd_fused_mix_bf16, W=1) == -2
+    assert fused16(L.cx_hier_sgd_fused_mix_f16, True, G=3) == -2 and fused16(L.cx_hier_sgd_fused_mix_f16, True, pe=None) == -1
+    assert fused16(L.cx_hier_sgd_fused_mix_bf16, True, G=16, W=32) == -8
+
     assert L.cx_copy_baseline(None, B, 64, None) == -1
     assert L.cx_copy_baseline(A, B, 6, None) == -2
     assert L.cx_copy_baseline(A, A + 64, 64, None) == -6
