@@ -48,12 +48,16 @@
  *              cx_check_segments / cx_check_peers before uploading.
  *   scratch    the out-of-place kernels keep a row-order table in library-owned device
  *              memory (static, per entry point 4 slots of 1 MiB per GPU), so no call
- *              allocates.  A slot is bound to the stream that first uses it; calls on one
- *              stream run in order, so a table is never rewritten while it is read.  Calls
- *              of one entry point on a fifth and later stream run without the table: same
- *              results, lower speed.  A call captured into a HIP graph keeps the slot of the
- *              stream it was captured on: replay the graph on that stream, or at least never
- *              while other calls of the same entry point run on it.
+ *              allocates.  A slot serves one stream at a time; calls on one stream run in
+ *              order, so a table is never rewritten while it is read.  A stream keeps its slot
+ *              while it has work in flight; when all slots are taken, the slot of a stream that
+ *              has drained or been destroyed changes hands, and a stream that finds none runs
+ *              without the table: same results, lower speed.  Calls recorded under stream
+ *              capture get a slot apart from the one their stream uses for eager calls and keep
+ *              it, so a captured graph may be replayed on any stream while eager calls go on;
+ *              graphs captured on ONE stream share that slot: replay them in one stream's order.
+ *              Matrices under 64 MiB run without the table (nothing to gain: they stay cached).
+ *              Host threads may call concurrently; the two launches of a call stay together.
  *   limits     at most CX_MAX_ROWS gossiping rows (W, or W/G in hierarchical mode).
  *   return     CX_OK (0) or a negative cx_status.  Argument errors are detected on the host
  *              before anything is enqueued.
@@ -327,7 +331,7 @@ int cx_hier_sgd_fused_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float
  *   key 4: in place: workgroup walks rows in lock-step (0/1)
  *   key 5: 1 = use the in-place kernel for out-of-place calls too
  *   key 6: out of place: chunks per cluster (1..4096)     key 7: out of place: XCD-aware block order (0/1)
- *   key 8: out of place: rows ordered along the permutation cycles (0/1)
+ *   key 8: out of place: rows ordered along the permutation cycles (0 never, 1 always; default: from 64 MiB)
  *   key 9: resident workgroups per CU, both kernels (1..16; 0 = as many as fit)
  * A (key 0, key 3) pair that an operator was not built with falls back to its default.
  * cx_set_tuning returns CX_ERR_SHAPE for an unknown key or value; a value of -1 restores

@@ -104,6 +104,25 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
+// Column (relative to the tile's first) of element q of slice u in this lane: eight or four
+// consecutive columns per lane, or the 4 + 4 split of the operators that pair 16-bit and fp32 rows.
+template <class Op, class = void>
+struct SplitSlices {
+    static constexpr bool value = false;
+};
+template <class Op>
+struct SplitSlices<Op, std::void_t<decltype(Op::kSplit)>> {
+    static constexpr bool value = Op::kSplit;
+};
+
+template <class Op>
+__device__ __forceinline__ int64_t column_of(int64_t c0, int lane, int u, int q)
+{
+    constexpr int kSliceCols = Op::kElems;
+    if constexpr (SplitSlices<Op>::value) return c0 + u * (kWave * kSliceCols) + (q >> 2) * 256 + 4 * lane + (q & 3);
+    else return c0 + kSliceCols * lane + u * (kWave * kSliceCols) + q;
+}
+
 // Orders LDS traffic between the lanes of ONE wavefront (wave-private LDS regions).
 __device__ __forceinline__ void wave_sync()
 {
@@ -519,7 +538,14 @@ __device__ __forceinline__ float to_f32_round_to_odd(double d)
     return __uint_as_float(bits);
 }
 
-// fp32 companion rows of 16-bit rows: slice u = 8 floats at p + u*512, two registers.
+// Column ownership of these operators ("split" slices): of every 512-column slice a lane owns
+// columns 4l..4l+3 and 256+4l..256+4l+3.  The 16-bit rows are then read with two 8-byte accesses
+// and the fp32 rows with two 16-byte ones, and every instruction of a wavefront covers one
+// contiguous 512-byte or 1-KB run.  (Eight consecutive columns per lane would suit the 16-bit rows
+// but leave each 16-byte access to the fp32 rows 32 bytes from its neighbour's: every cache line
+// requested twice, measured 7 % slower on the fused step.)  `p` = row base + tile start + 4*lane
+// (the kernels hand every operator the column of its lane's first element: column_of);
+// element e of slice u is column u*512 + (e/4)*256 + 4*lane + e%4 of the tile.
 template <int U, bool FULL, bool NT>
 __device__ __forceinline__ void tile_load8(const float *p, const unsigned (&mask)[U], Tile<2 * U> &t)
 {
@@ -527,7 +553,7 @@ __device__ __forceinline__ void tile_load8(const float *p, const unsigned (&mask
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-            const float *q = p + u * (kWave * 8) + 4 * hh;
+            const float *q = p + u * (kWave * 8) + 256 * hh;
             if constexpr (FULL) {
                 const f4 *q4 = reinterpret_cast<const f4 *>(q);
                 t.v[2 * u + hh] = NT ? __builtin_nontemporal_load(q4) : *q4;
@@ -545,7 +571,7 @@ __device__ __forceinline__ void tile_store8(float *p, const unsigned (&mask)[U],
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-            float *q = p + u * (kWave * 8) + 4 * hh;
+            float *q = p + u * (kWave * 8) + 256 * hh;
             if constexpr (FULL) {
                 f4 *q4 = reinterpret_cast<f4 *>(q);
                 if (NT) __builtin_nontemporal_store(t.v[2 * u + hh], q4); else *q4 = t.v[2 * u + hh];
@@ -557,7 +583,59 @@ __device__ __forceinline__ void tile_store8(float *p, const unsigned (&mask)[U],
         }
 }
 
-// columns 4*hh .. 4*hh+3 of a packed 16-bit slice, widened exactly to doubles
+// the 16-bit rows in the same ownership: words 0, 1 of the register = the first four columns,
+// words 2, 3 = the second four
+template <int U, bool FULL, bool NT>
+__device__ __forceinline__ void tile_load16_split(const uint16_t *p, const unsigned (&mask)[U], Tile<U> &raw)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        u4 w = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const uint16_t *q = p + u * (kWave * 8) + 256 * hh;
+            if constexpr (FULL) {
+                const u2 *q2 = reinterpret_cast<const u2 *>(q);
+                const u2 two = NT ? __builtin_nontemporal_load(q2) : *q2;
+                w[2 * hh] = two[0];
+                w[2 * hh + 1] = two[1];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((mask[u] >> (4 * hh + e)) & 1u) w[2 * hh + (e >> 1)] |= static_cast<unsigned>(q[e]) << (16 * (e & 1));
+            }
+        }
+        raw.v[u] = __builtin_bit_cast(f4, w);
+    }
+}
+
+template <int U, bool FULL, bool NT>
+__device__ __forceinline__ void tile_store16_split(uint16_t *p, const unsigned (&mask)[U], const Tile<U> &raw)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const u4 w = __builtin_bit_cast(u4, raw.v[u]);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            uint16_t *q = p + u * (kWave * 8) + 256 * hh;
+            if constexpr (FULL) {
+                u2 *q2 = reinterpret_cast<u2 *>(q);
+                const u2 two = {w[2 * hh], w[2 * hh + 1]};
+                if (NT) __builtin_nontemporal_store(two, q2); else *q2 = two;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((mask[u] >> (4 * hh + e)) & 1u) q[e] = static_cast<uint16_t>(w[2 * hh + (e >> 1)] >> (16 * (e & 1)));
+            }
+        }
+    }
+}
+
+// half hh (words 2*hh, 2*hh+1) of a packed 16-bit slice, widened exactly to doubles
 template <bool IEEE_HALF>
 __device__ __forceinline__ d4 widen16_half(const f4 &packed, int hh)
 {
@@ -601,6 +679,7 @@ struct Fused16Op {
     static constexpr GatherShape kGather{1, 8, 192, 0};
     static constexpr WalkShape kWalk{1, 2, 4, 2};
     static constexpr int kMaxU = 1;
+    static constexpr bool kSplit = true;                   // lanes own 4 + 4 columns of a slice (see tile_load8)
     template <int U> struct Raw { Tile<U> x, g; Tile<2 * U> v; };
     const uint16_t *xin;
     uint16_t *xout;
@@ -614,9 +693,9 @@ struct Fused16Op {
     __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
     {
         const int64_t o = static_cast<int64_t>(row) * ld + off;
-        tile_load16<U, FULL, NT>(xin + o, mask, raw.x);
+        tile_load16_split<U, FULL, NT>(xin + o, mask, raw.x);
         tile_load8<U, FULL, NT>(vin + o, mask, raw.v);
-        tile_load16<U, FULL, NT>(g + o, mask, raw.g);
+        tile_load16_split<U, FULL, NT>(g + o, mask, raw.g);
     }
     template <int U, bool FULL, bool NT, bool COMMIT = true>
     __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
@@ -630,7 +709,8 @@ struct Fused16Op {
                 t.v[2 * u + hh] = sgd.apply(widen16_half<IEEE_HALF>(raw.x.v[u], hh), v, widen16_half<IEEE_HALF>(raw.g.v[u], hh));
                 v32.v[2 * u + hh] = narrow(v);
             }
-        if constexpr (COMMIT) tile_store8<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
+        if constexpr (COMMIT)
+            tile_store8<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
     }
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
@@ -638,7 +718,7 @@ struct Fused16Op {
         Tile<U> packed;
 #pragma unroll
         for (int u = 0; u < U; ++u) packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
-        tile_store16<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
+        tile_store16_split<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
     }
 };
 
@@ -652,6 +732,7 @@ struct HierFused16Op {
         G == 1 ? GatherShape{1, 8, 192, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
     static constexpr WalkShape kWalk{1, 2, 2, 2};
     static constexpr int kMaxU = 1;
+    static constexpr bool kSplit = true;
     template <int U> struct Raw { Tile<U> g[G], x; Tile<2 * U> v; };
     const uint16_t *xin;
     uint16_t *xout;
@@ -666,8 +747,8 @@ struct HierFused16Op {
     {
         const int64_t lead = static_cast<int64_t>(row) * G * ld + off;
 #pragma unroll
-        for (int j = 0; j < G; ++j) tile_load16<U, FULL, NT>(g + lead + j * ld, mask, raw.g[j]);
-        tile_load16<U, FULL, NT>(xin + lead, mask, raw.x);
+        for (int j = 0; j < G; ++j) tile_load16_split<U, FULL, NT>(g + lead + j * ld, mask, raw.g[j]);
+        tile_load16_split<U, FULL, NT>(xin + lead, mask, raw.x);
         tile_load8<U, FULL, NT>(vin + static_cast<int64_t>(row) * ld + off, mask, raw.v);
     }
     template <int U, bool FULL, bool NT, bool COMMIT = true>
@@ -686,7 +767,8 @@ struct HierFused16Op {
                 t.v[2 * u + hh] = sgd.apply(widen16_half<IEEE_HALF>(raw.x.v[u], hh), v, gbar);
                 v32.v[2 * u + hh] = narrow(v);
             }
-        if constexpr (COMMIT) tile_store8<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
+        if constexpr (COMMIT)
+            tile_store8<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
     }
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
@@ -696,7 +778,7 @@ struct HierFused16Op {
         for (int u = 0; u < U; ++u) packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
         uint16_t *p = xout + static_cast<int64_t>(row) * G * ld + off;
 #pragma unroll
-        for (int j = 0; j < G; ++j) tile_store16<U, FULL, NT>(p + j * ld, mask, packed);
+        for (int j = 0; j < G; ++j) tile_store16_split<U, FULL, NT>(p + j * ld, mask, packed);
     }
 };
 
@@ -837,7 +919,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
             unsigned mask[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) mask[u] = (1u << kSliceCols) - 1u;
-            walk<Op, U, D, true, NT, true>(op, sched, n, skip_mix != 0, tile * kTileCols + kSliceCols * lane, mask);
+            walk<Op, U, D, true, NT, true>(op, sched, n, skip_mix != 0, column_of<Op>(tile * kTileCols, lane, 0, 0), mask);
             return;
         }
     }
@@ -847,7 +929,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
 
     const int64_t c0 = tile * kTileCols;
     const int64_t c1 = (c0 + kTileCols < P) ? c0 + kTileCols : P;
-    const int64_t off = c0 + kSliceCols * lane;
+    const int64_t off = column_of<Op>(c0, lane, 0, 0);     // this lane's first column
 
     // segment that holds column c0: number of interior boundaries <= c0
     int lo = 1, hi = S;
@@ -876,7 +958,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void mix_kernel(
                 mask[u] = 0;
 #pragma unroll
                 for (int q = 0; q < kSliceCols; ++q) {
-                    const int64_t c = off + u * (kWave * kSliceCols) + q;
+                    const int64_t c = column_of<Op>(c0, lane, u, q);
                     if (c >= b && c < e) mask[u] |= 1u << q;
                 }
             }
@@ -993,7 +1075,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
     const int64_t c0 = static_cast<int64_t>(chunk * nwaves + wave) * kTileCols;
     if (chunk >= nchunks || c0 >= P) return;
     const int64_t c1 = (c0 + kTileCols < P) ? c0 + kTileCols : P;
-    const int64_t off = c0 + kSliceCols * lane;
+    const int64_t off = column_of<Op>(c0, lane, 0, 0);     // this lane's first column
     unsigned full_mask[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) full_mask[u] = (1u << kSliceCols) - 1u;
@@ -1101,7 +1183,7 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
             mask[u] = 0;
 #pragma unroll
             for (int q = 0; q < kSliceCols; ++q) {
-                const int64_t c = off + u * (kWave * kSliceCols) + q;
+                const int64_t c = column_of<Op>(c0, lane, u, q);
                 if (c >= sb && c < se) mask[u] |= 1u << q;
             }
         }
@@ -1251,36 +1333,42 @@ std::mutex &enqueue_mutex()
 
 // The order table `stream` may write on the current device, or nullptr (run without one).
 // A stream keeps the slot it used last.  When every slot belongs to another stream, a slot
-// whose owner has no work in flight (or no longer exists) changes hands; a slot that was ever
-// used under stream capture stays with its stream, since the captured graph names it.
+// whose owner has no work in flight (or no longer exists) changes hands.  Calls recorded under
+// stream capture get a slot of their own, apart from the one the same stream uses for eager
+// calls, and keep it for good: the captured graph names it, and may be replayed on any stream
+// while eager calls go on.  (Graphs captured on ONE stream share that slot: replay them in
+// one stream's order.)
 unsigned *order_table_for(hipStream_t stream)
 {
-    static hipStream_t owner[kMaxDevices][kOrderSlots];
-    static bool used[kMaxDevices][kOrderSlots], pinned[kMaxDevices][kOrderSlots];
+    struct Slot {
+        hipStream_t owner;
+        bool used, for_capture;
+    };
+    static Slot slots[kMaxDevices][kOrderSlots];
     int dev = 0;
     unsigned *base = order_tables_base(&dev);
     if (!base) return nullptr;
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     const bool capturing = hipStreamIsCapturing(stream, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
+    Slot *mine = slots[dev];
     int slot = -1;
     for (int i = 0; i < kOrderSlots && slot < 0; ++i)
-        if (used[dev][i] && owner[dev][i] == stream) slot = i;
+        if (mine[i].used && mine[i].owner == stream && mine[i].for_capture == capturing) slot = i;
     for (int i = 0; i < kOrderSlots && slot < 0; ++i)
-        if (!used[dev][i]) slot = i;
-    for (int i = 0; i < kOrderSlots && slot < 0; ++i) {
-        if (pinned[dev][i]) continue;
+        if (!mine[i].used) slot = i;
+    // (no questions about other streams while this one records: a capture forbids them)
+    for (int i = 0; i < kOrderSlots && slot < 0 && !capturing; ++i) {
+        if (mine[i].for_capture) continue;                                        // a graph names it
         hipStreamCaptureStatus ocs = hipStreamCaptureStatusNone;
-        const hipError_t q = hipStreamIsCapturing(owner[dev][i], &ocs);
+        const hipError_t q = hipStreamIsCapturing(mine[i].owner, &ocs);
         if (q == hipSuccess && ocs != hipStreamCaptureStatusNone) continue;       // recording: leave it
-        const hipError_t busy = q == hipSuccess ? hipStreamQuery(owner[dev][i]) : q;
+        const hipError_t busy = q == hipSuccess ? hipStreamQuery(mine[i].owner) : q;
         if (busy == hipErrorNotReady) continue;                                   // work in flight
         if (busy != hipSuccess) (void)hipGetLastError();                          // the stream is gone
         slot = i;
     }
     if (slot < 0) return nullptr;
-    owner[dev][slot] = stream;
-    used[dev][slot] = true;
-    if (capturing) pinned[dev][slot] = true;
+    mine[slot] = Slot{stream, true, capturing};
     return base + static_cast<int64_t>(slot) * kOrderEntries;
 }
 

@@ -178,6 +178,7 @@ def test_rounds_captured_in_a_hip_graph_replay_like_eager():
     a, b = dev(x), dev(x)
     c = dev(x)
     x0 = dev(x)
+    cx.cx_set_tuning(cx.TUNE_ORDERED, 1)       # small matrix: ask for the row-order table all the same
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):              # warm up on the capture stream
@@ -191,6 +192,7 @@ def test_rounds_captured_in_a_hip_graph_replay_like_eager():
             cx.cx_gossip_mix(a, b, P, sod, tds[r])
             a, b = b, a
             cx.cx_gossip_mix(c, c, P, sod, tds[r])
+    cx.cx_set_tuning(cx.TUNE_ORDERED, -1)
     for replay in range(3):
         a.copy_(x0)
         c.copy_(x0)
@@ -236,13 +238,68 @@ def test_out_of_place_calls_on_more_streams_than_order_table_slots():
     outs = [torch.empty_like(a) for a in ins]
     tds = [dev(t) for t in tabs]
     torch.cuda.synchronize()
-    for rep in range(2):            # second pass: every stream meets its slot (or none) again
-        for st, a, b, t in zip(streams, ins, outs, tds):
-            with torch.cuda.stream(st):
-                cx.cx_gossip_mix(a, b, P, sod, t, stream=st)
+    with Tuning(ordered=1):
+        for rep in range(3):        # later passes: streams meet their slot again, or take over a drained one
+            for st, a, b, t in zip(streams, ins, outs, tds):
+                with torch.cuda.stream(st):
+                    cx.cx_gossip_mix(a, b, P, sod, t, stream=st)
     torch.cuda.synchronize()
     for b, t in zip(outs, tabs):
         assert same_bits(host(b)[:, :P], O.gossip_mix(x, P, so, t)[:, :P])
+
+
+def test_short_lived_streams_do_not_use_up_the_order_tables():
+    """Slots of streams that have drained or been destroyed change hands: after many short-lived
+    streams a new stream still gets a table (same results either way; this checks the results)."""
+    W, P, S = 8, 20011, 3
+    x = WL.gen_matrix(W, P, 1.0, seed=29, ld=20480)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(29, W, S, 0, 10)
+    sod, xd = dev(so), dev(x)
+    with Tuning(ordered=1):
+        for r in range(10):
+            st = torch.cuda.Stream()
+            out = torch.empty_like(xd)
+            with torch.cuda.stream(st):
+                cx.cx_gossip_mix(xd, out, P, sod, dev(tabs[r]), stream=st)
+            st.synchronize()
+            assert same_bits(host(out)[:, :P], O.gossip_mix(x, P, so, tabs[r])[:, :P]), r
+            del st
+
+
+def test_graph_replayed_on_another_stream_next_to_eager_calls():
+    """A captured call keeps an order table of its own, apart from the one its stream uses for eager
+    calls: replaying the graph on a second stream while eager calls with OTHER peer tables run on the
+    capture stream must leave both results right."""
+    W, P, S, R = 32, 1_000_003, 4, 6
+    ld = (P + 1023) // 1024 * 1024
+    x = WL.gen_matrix_device(W, P, 1.0, seed=30, ld=ld)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(30, W, S, 0, 2)
+    sod, t0, t1 = dev(so), dev(tabs[0]), dev(tabs[1])
+    xh = host(x)
+    want0 = O.gossip_mix(xh, P, so, tabs[0])[:, :P]
+    want1 = O.gossip_mix(xh, P, so, tabs[1])[:, :P]
+    out_graph, out_eager = torch.empty_like(x), torch.empty_like(x)
+    side, other = torch.cuda.Stream(), torch.cuda.Stream()
+    with Tuning(ordered=1):
+        with torch.cuda.stream(side):
+            cx.cx_gossip_mix(x, out_eager, P, sod, t1, stream=side)         # the eager slot of `side`
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            cx.cx_gossip_mix(x, out_graph, P, sod, t0)
+        for _ in range(R):
+            out_graph.fill_(float("nan"))
+            out_eager.fill_(float("nan"))
+            torch.cuda.synchronize()
+            with torch.cuda.stream(other):
+                g.replay()
+            with torch.cuda.stream(side):
+                for _ in range(3):
+                    cx.cx_gossip_mix(x, out_eager, P, sod, t1, stream=side)
+            torch.cuda.synchronize()
+            assert same_bits(host(out_graph)[:, :P], want0) and same_bits(host(out_eager)[:, :P], want1)
 
 
 # ----------------------------------------------------------------------- bfloat16 rows
