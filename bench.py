@@ -39,6 +39,11 @@ def dtype_of(kind, rows16) -> str:
     return arith if arith == "f32" else "f64 (f32 rows in HBM)"
 
 
+def entry_point(kind, rows16) -> str:
+    return {"fused": "cx_sgd_fused_mix", "hiersgd": "cx_hier_sgd_fused_mix"}.get(kind, f"cx_{kind}_mix") + (
+        "_" + rows16 if rows16 else "")
+
+
 def describe(wl, rows="fp32") -> str:
     s = f"{wl.name}: W={wl.W} P={wl.P} {rows} S={wl.S}"
     if wl.G > 1:
@@ -76,26 +81,22 @@ class Runner:
         self.tab_host = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, pin_memory=True)
         self.tab_np = self.tab_host.numpy()
         self.tab_dev = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, device=dev)
-        self.bytes_per_elem = 4 if rows16 else 8
+        self.bytes_per_elem = bytes_per_element(kind, wl.G, rows16)
         dt16 = (torch.bfloat16 if rows16 == "bf16" else torch.float16) if rows16 else None
         if kind == "fused":
             self.v = torch.zeros((wl.W, self.ld), device=dev)              # the momentum stays fp32
             self.v2 = self.v if in_place else torch.empty_like(self.v)
             self.g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
-            self.bytes_per_elem = 20
             if rows16:
                 self.g = self.g.to(dt16)
-                self.bytes_per_elem = 14                                   # read x, g (2 B) and v (4 B); write x, v
         if kind == "hiersgd":
             c4 = WL.WORKLOADS["C4"]            # optimizer constants and gradient scale of C4
             self.lr, self.mu, self.wd = c4.lr, c4.mu, c4.wd
-            self.bytes_per_elem = 8 + 12.0 / wl.G
             self.v = torch.zeros((wl.L, self.ld), device=dev)
             self.v2 = self.v if in_place else torch.empty_like(self.v)
             self.g = WL.gen_matrix_device(wl.W, wl.P, c4.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
             if rows16:
                 self.g = self.g.to(dt16)
-                self.bytes_per_elem = 4 + 10.0 / wl.G
         if kind == "pushsum":
             self.w = [torch.ones(wl.W, device=dev), torch.zeros(wl.W, device=dev)]
         self.round = 0
@@ -164,19 +165,60 @@ class Runner:
             "alg_bytes_per_launch": alg_bytes,
         }
 
+    def whole_step_latency(self, rounds):
+        """One step at a time, the device idle before and after: host clock around topology generation,
+        table upload, launch and completion.  Median and minimum over `rounds` steps, in ms."""
+        torch = self.torch
+        lat = []
+        for _ in range(rounds):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.step(False)
+            torch.cuda.synchronize()
+            lat.append((time.perf_counter() - t0) * 1e3)
+        return {"median": float(np.median(lat)), "min": float(np.min(lat)), "rounds": rounds}
 
-def measured_traffic(workload, kind, in_place, rows16=None):
-    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE, scaled by the copy-kernel calibration), or None if there is none for this case."""
-    name = f"{workload}_{kind}{'_' + rows16 if rows16 else ''}_{'inplace' if in_place else 'pingpong'}_pmc.txt"
+
+def kernel_source_id():
+    """Short hash of the kernel sources: a profile summary carries the one it was taken with."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2012_15198_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hpp", ".hip")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profile_name(workload, kind, in_place, rows16=None):
+    return f"{workload}_{kind}{'_' + rows16 if rows16 else ''}_{'inplace' if in_place else 'pingpong'}"
+
+
+def profiled_traffic(workload, kind, in_place, rows16=None, tuning=None):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload and entry
+    point (FETCH_SIZE and WRITE_SIZE, scaled by the copy-kernel calibration).  The figure is NOT measured
+    in this run, so it is reported only if the summary was taken with the kernel sources as they are now
+    and with default launch parameters; otherwise (None, why)."""
+    name = profile_name(workload, kind, in_place, rows16) + "_pmc.txt"
     path = os.path.join(ROOT, "profiles", name)
+    if tuning:
+        return None, "launch parameters changed with --tune: no profile for them"
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+        lines = open(path).read().splitlines()
     except OSError:
-        pass
-    return None
+        return None, f"no profiles/{name}"
+    traffic = src = None
+    for line in lines:
+        if line.startswith("traffic_bytes_per_launch:"):
+            traffic = float(line.split(":")[1])
+        if line.startswith("kernel_source_id:"):
+            src = line.split(":")[1].strip()
+    if traffic is None:
+        return None, f"profiles/{name} holds no traffic figure"
+    if src != kernel_source_id():
+        return None, f"profiles/{name} was taken with kernel sources {src}, these are {kernel_source_id()}"
+    return traffic, f"profiles/{name} (kernel sources {src})"
 
 
 def copy_ceiling(nbytes, reps=10):
@@ -221,28 +263,101 @@ def topology_gen_time(runner):
             "host_us_per_round": best * 1e6 / wl.rounds}
 
 
-def cpu_baseline(runner, budget_s=12.0):
-    """The CPU oracle, as it stands, timed on this host: full rounds of the same workload."""
+def cpu_baseline(wl, kind, rows16=None, budget_s=12.0, max_bytes=8 << 30):
+    """The CPU oracle, as it stands, timed on this host on the entry point's own function: full rounds of
+    the workload where a round's matrices fit `max_bytes`, otherwise on the first columns of every row
+    (mixing is independent per column; segments are cut at the last column taken).  Inputs are drawn on
+    the host with the workload's recipe."""
     import oracle as O
-    wl = runner.wl
-    x = runner.x.cpu().numpy()
-    out = np.empty_like(x)
-    tabs = O.topology(wl.seed, wl.W, wl.S, 0, 64)
-    O.gossip_mix(x, wl.P, runner.so_host, tabs[0], out=out)      # touch the pages
+    from paper_2012_15198_amd import workloads as WL
+    c4 = WL.WORKLOADS["C4"]
+    lr, mu, wd = (wl.lr, wl.mu, wl.wd) if wl.lr else (c4.lr, c4.mu, c4.wd)
+    mats = {"gossip": 1, "hier": 1, "pushsum": 1, "fused": 3, "hiersgd": 2 + 1.0 / wl.G}[kind]
+    n = wl.L if kind in ("hier", "hiersgd") else wl.W
+    S = 1 if kind == "pushsum" else wl.S
+    fmt = rows16
+    narrow = {None: lambda a: a, "bf16": lambda a: (a.view(np.uint32) >> 16).astype(np.uint16),
+              "f16": lambda a: a.astype(np.float16).view(np.uint16)}[fmt]       # input preparation only
+    tabs = O.topology(wl.seed, n, S, 0, 16, 1 if kind == "pushsum" else 0)
+    name = {"gossip": "oracle_gossip_mix", "hier": "oracle_hier_mix_f32", "pushsum": "oracle_pushsum_mix_f32",
+            "fused": "oracle_sgd_fused_mix_f64", "hiersgd": "oracle_hier_sgd_fused_mix_f64"}[kind]
+    if fmt:
+        name = {"gossip": f"oracle_gossip_mix_{fmt}", "hier": "oracle_hier_mix16_f32", "fused": "oracle_sgd_fused_mix16",
+                "hiersgd": "oracle_hier_sgd_fused_mix16"}[kind]
+    x = v = g = so = spare = None
+    w = np.ones(wl.W, dtype=np.float32)
+    P = 0
+
+    def draw(cols):
+        nonlocal x, v, g, so, P, spare
+        P, spare = cols, None
+        so = np.minimum(WL.seg_off_for(wl), P).astype(np.int64)
+        x = narrow(WL.gen_matrix(wl.W, P, wl.sigma, wl.seed))
+        if kind in ("fused", "hiersgd"):
+            g = narrow(WL.gen_matrix(wl.W, P, wl.grad_sigma or c4.grad_sigma, wl.seed, stream=2))
+            v = np.zeros((n if kind == "hiersgd" else wl.W, P), dtype=np.float32)
+
+    def one_round(r):
+        nonlocal x, v, w
+        t = tabs[r % 16]
+        nonlocal spare
+        if kind == "gossip" and not fmt:
+            if spare is None:
+                spare = np.empty_like(x)
+            spare = O.gossip_mix(x, P, so, t, out=spare)          # two buffers in turn, as on the device
+            x, spare = spare, x
+        elif kind == "gossip":
+            x = (O.gossip_mix_bf16 if fmt == "bf16" else O.gossip_mix_f16)(x, P, so, t)
+        elif kind == "hier":
+            x = O.hier_mix_f32(x, P, wl.G, so, t) if not fmt else O.hier_mix16_f32(fmt, x, P, wl.G, so, t)
+        elif kind == "pushsum":
+            x, w, _ = O.pushsum_mix_f32(x, w, P, int((0 - int(t[0, 0])) % wl.W), False)
+        elif kind == "fused":
+            if fmt:
+                x, v = O.sgd_fused_mix16(fmt, x, v, g, lr, mu, wd, P, so, t)
+            else:
+                x, v = (a.astype(np.float32) for a in O.sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, so, t))
+        else:
+            if fmt:
+                x, v = O.hier_sgd_fused_mix16(fmt, x, v, g, lr, mu, wd, P, wl.G, so, t)
+            else:
+                x, v = (a.astype(np.float32) for a in O.hier_sgd_fused_mix_f64(x, v, g, lr, mu, wd, P, wl.G, so, t))
+
+    # size of the sample: what memory allows, cut down so that a round takes about a quarter of the budget
+    cols = int(min(wl.P, max_bytes // (4 * wl.W * mats * 2)))           # inputs and outputs
+    probe = min(cols, 16384)
+    draw(probe)
+    t0 = time.perf_counter()
+    one_round(0)
+    per_col = (time.perf_counter() - t0) / probe
+    cols = int(max(probe, min(cols, budget_s / 4 / per_col)))
+    draw(cols)
+    one_round(0)                                                      # touch the pages
     rounds, t0 = 0, time.perf_counter()
     while True:
-        O.gossip_mix(x, wl.P, runner.so_host, tabs[(rounds + 1) % 64], out=out)
-        x, out = out, x
+        one_round(rounds + 1)
         rounds += 1
         dt = time.perf_counter() - t0
         if dt > budget_s or rounds >= 40:
             break
-    elems = wl.W * wl.P
-    return {"value": 8.0 * elems * rounds / dt / 1e9, "unit": "GB/s",
+    bpe = bytes_per_element(kind, wl.G, rows16)
+    elems = wl.W * P
+    what = "full rounds" if P == wl.P else f"rounds on columns [0, {P}) of every row ({100.0 * P / wl.P:.1f} % of the matrix)"
+    return {"value": bpe * elems * rounds / dt / 1e9, "unit": "GB/s",
             "params_mixed_per_s": elems * rounds / dt, "s_per_round": dt / rounds,
+            "s_per_full_round": dt / rounds * wl.P / P,
             "cores": 1, "kind": "oracle",
-            "sample": f"{rounds} full rounds of {describe(wl)} (oracle_gossip_mix, single thread, "
+            "sample": f"{rounds} {what} of {describe(wl, rows16 or 'fp32')} ({name}, single thread, "
                       f"{os.cpu_count()} host cores visible, {cpu_model()})"}
+
+
+def bytes_per_element(kind, G, rows16):
+    """Algorithmic bytes per worker-parameter and round: every element read once and written once."""
+    if kind == "fused":
+        return 14 if rows16 else 20                   # x, v, g in; x, v out (16-bit x and g, fp32 v)
+    if kind == "hiersgd":
+        return 4 + 10.0 / G if rows16 else 8 + 12.0 / G
+    return 4 if rows16 else 8
 
 
 def main():
@@ -285,8 +400,10 @@ def main():
     rows16 = "bf16" if args.bf16 else "f16" if args.f16 else None
     if rows16 and kind == "pushsum":
         sys.exit("bench.py: --bf16 / --f16 are not available for the push-sum comparison")
-    runner = Runner(wl, kind, args.steps + args.warmup, in_place=args.in_place, rows16=rows16)
+    latency_rounds = min(wl.rounds, 20)
+    runner = Runner(wl, kind, args.steps + args.warmup + latency_rounds, in_place=args.in_place, rows16=rows16)
     res = runner.run(args.steps, args.warmup)
+    traffic, traffic_source = profiled_traffic(wl.name, kind, args.in_place, rows16, tuning)
     out = {
         "metric": "gossip-mix HBM GB/s and params-mixed/s per round (fraction of HBM peak), 1 GPU",
         "value": res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -295,8 +412,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": describe(wl, rows16 or "fp32") if kind != "gossip" or wl.G == 1
                    else describe(wl, rows16 or "fp32") + " (flat gossip over all rows)",
-                   "entry_point": {"fused": "cx_sgd_fused_mix", "hiersgd": "cx_hier_sgd_fused_mix"}.get(
-                       kind, f"cx_{kind}_mix") + ("_" + rows16 if rows16 else ""),
+                   "entry_point": entry_point(kind, rows16),
                    "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
                    "buffers": "in place" if args.in_place else "ping-pong (x_in -> x_out, swapped every round)",
                    "step": "cx_topology_gen(1 round) + table upload + one mixing launch",
@@ -305,40 +421,46 @@ def main():
         "frac_of_hbm_peak": res["GBps"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": res["kernel_GBps"], "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": res["kernel_GBps"] / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic(wl.name, kind, args.in_place, rows16),
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "profiled_traffic_GBps": traffic / (res["kernel_ms_avg"] * 1e-3) / 1e9 if traffic else None,
                      "kernel": "mix_kernel" if args.in_place else "gather_kernel",
                      "kernel_ms_avg": res["kernel_ms_avg"],
                      "kernel_ms_min": res["kernel_ms_min"], "kernel_ms_median": res["kernel_ms_median"],
                      "alg_bytes_per_launch": res["alg_bytes_per_launch"]},
     }
-    traffic = out["roofline"]["traffic"]
-    out["roofline"]["measured_GBps"] = traffic / (res["kernel_ms_avg"] * 1e-3) / 1e9 if traffic else None
+    out["whole_step_latency_ms"] = runner.whole_step_latency(latency_rounds)
     out["topology_gen"] = topology_gen_time(runner)
     if not args.no_copy:
         out["copy_ceiling"] = copy_ceiling(res["alg_bytes_per_launch"])
-    if not args.no_cpu_baseline and kind == "gossip" and not rows16:
-        out["cpu_baseline"] = cpu_baseline(runner)
-    else:
-        out["cpu_baseline"] = None
     del runner
     torch.cuda.empty_cache()
+    out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(wl, kind, rows16)
 
     if args.all:
+        # every other workload and entry point: events around each round's call over the workload's own
+        # number of rounds (median and minimum), the whole-step latency, and the oracle on the host
         others = {}
-        plan = [("C1", "gossip", None, 50), ("C2", "gossip", "bf16", 50), ("C2", "gossip", "f16", 50),
-                ("C3", "hier", None, 20), ("C3", "hier", "bf16", 20), ("C3", "hiersgd", None, 20),
-                ("C4", "fused", None, 10), ("C4", "pushsum", None, 20), ("C5", "hier", None, 10)]
-        for name, k, r16, steps in plan:
+        plan = [("C1", "gossip", None), ("C2", "gossip", None), ("C2", "gossip", "bf16"), ("C2", "gossip", "f16"),
+                ("C3", "hier", None), ("C3", "hier", "bf16"), ("C3", "hiersgd", None), ("C3", "hiersgd", "bf16"),
+                ("C4", "fused", None), ("C4", "fused", "bf16"), ("C4", "pushsum", None), ("C5", "hier", None)]
+        for name, k, r16 in plan:
             if name == args.workload and k == kind and r16 == rows16:
                 continue
-            r = Runner(WL.WORKLOADS[name], k, steps + 3, in_place=args.in_place, rows16=r16)
-            rr = r.run(steps, 3)
-            rr["workload"] = describe(WL.WORKLOADS[name], r16 or "fp32")
+            w2 = WL.WORKLOADS[name]
+            r = Runner(w2, k, 2 * w2.rounds + 3, in_place=args.in_place, rows16=r16)
+            rr = r.run(w2.rounds, 3)
+            rr["workload"] = describe(w2, r16 or "fp32")
+            rr["entry_point"] = entry_point(k, r16)
+            rr["rounds"] = w2.rounds
             rr["frac_of_hbm_peak_kernel"] = rr["kernel_GBps"] / HBM_PEAK_GBPS
-            rr["traffic"] = measured_traffic(name, k, args.in_place, r16)
-            others[f"{name}:{k}" + (f":{r16}" if r16 else "")] = rr
+            rr["frac_of_hbm_peak_kernel_median"] = rr["alg_bytes_per_launch"] / (rr["kernel_ms_median"] * 1e-3) / 1e9 / HBM_PEAK_GBPS
+            rr["whole_step_latency_ms"] = r.whole_step_latency(w2.rounds)
+            rr["traffic"], rr["traffic_source"] = profiled_traffic(name, k, args.in_place, r16, tuning)
             del r
             torch.cuda.empty_cache()
+            if not args.no_cpu_baseline:
+                rr["cpu_baseline"] = cpu_baseline(w2, k, r16, budget_s=5.0)
+            others[f"{name}:{k}" + (f":{r16}" if r16 else "")] = rr
         out["other_workloads"] = others
     print(json.dumps(out))
 
