@@ -63,7 +63,7 @@ void fair_table(const DrawStream &rng, int32_t n, int32_t *recv_from, std::vecto
     }
 }
 
-constexpr int kTuningKeys = 10;
+constexpr int kTuningKeys = 11;
 // Random topology WITHOUT fair peer selection: every row draws independently among the
 // other n-1 rows, so rows may be picked twice or never (the paper's comparison case).
 void unfair_table(const DrawStream &rng, int32_t n, int32_t *recv_from)
@@ -74,7 +74,7 @@ void unfair_table(const DrawStream &rng, int32_t n, int32_t *recv_from)
     }
 }
 
-std::atomic<int32_t> g_tuning[kTuningKeys] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
+std::atomic<int32_t> g_tuning[kTuningKeys] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
 
 }  // namespace
 
@@ -174,7 +174,7 @@ int cx_set_tuning(int32_t key, int32_t value)
         if (key == 1 && (value < 1 || value > 8)) return CX_ERR_SHAPE;
         if (key == 2 && value != 0 && value != 1) return CX_ERR_SHAPE;
         if (key == 3 && value != 2 && value != 4 && value != 8) return CX_ERR_SHAPE;
-        if ((key == 4 || key == 5 || key == 7 || key == 8) && value != 0 && value != 1) return CX_ERR_SHAPE;
+        if ((key == 4 || key == 5 || key == 7 || key == 8 || key == 10) && value != 0 && value != 1) return CX_ERR_SHAPE;
         if (key == 6 && (value < 1 || value > 4096)) return CX_ERR_SHAPE;
         if (key == 9 && (value < 0 || value > 16)) return CX_ERR_SHAPE;
     }

@@ -245,6 +245,67 @@ struct MeanOp {
     }
 };
 
+// The hierarchical mean staged through LDS, kept for measurement next to the register tree (launch
+// parameter 10).  A workgroup is G wavefronts and owns G tiles of 256 columns; wavefront j fetches
+// row j of its group and of the partner group (G contiguous 1-KB loads each), the rows meet in
+// LDS (G x G KB), wavefront w reduces tile w over the G rows with the same pairwise tree, and the
+// result travels back through LDS so that wavefront j stores row j.  Same arithmetic in the
+// same order as MeanOp<G>, hence the same bits; five barriers per workgroup.  Chunks that a
+// segment boundary or the row end crosses take MeanOp<G>'s register path.
+template <int G>
+struct MeanLdsOp : MeanOp<G> {
+    static constexpr bool kLdsStaged = true;
+    static constexpr size_t kLdsBytes = static_cast<size_t>(G) * G * kWave * sizeof(f4);
+
+    template <bool NT>
+    __device__ __forceinline__ void lds_mix(int row, int peer, int64_t chunk_c0, int lane, int wave, f4 *lds) const
+    {
+        const int64_t col = chunk_c0 + 4 * lane;
+        const float *own = this->xin + (static_cast<int64_t>(row) * G + wave) * this->ld + col;
+        const float *oth = this->xin + (static_cast<int64_t>(peer) * G + wave) * this->ld + col;
+        f4 mine[G], theirs[G];
+#pragma unroll
+        for (int t = 0; t < G; ++t) mine[t] = *reinterpret_cast<const f4 *>(own + t * 256);
+#pragma unroll
+        for (int t = 0; t < G; ++t) theirs[t] = *reinterpret_cast<const f4 *>(oth + t * 256);
+        Tile<1> r[G];
+#pragma unroll
+        for (int t = 0; t < G; ++t) lds[(wave * G + t) * kWave + lane] = mine[t];        // [row][tile][lane]
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < G; ++j) r[j].v[0] = lds[(j * G + wave) * kWave + lane];
+        const f4 a = tree_sum<G, 1>(r).v[0] * this->inv_g;
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < G; ++t) lds[(wave * G + t) * kWave + lane] = theirs[t];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < G; ++j) r[j].v[0] = lds[(j * G + wave) * kWave + lane];
+        const f4 c = tree_sum<G, 1>(r).v[0] * this->inv_g;
+        __syncthreads();
+        lds[wave * kWave + lane] = average(a, c);                                        // result tile `wave`
+        __syncthreads();
+        float *dst = this->xout + (static_cast<int64_t>(row) * G + wave) * this->ld + col;
+#pragma unroll
+        for (int t = 0; t < G; ++t) {
+            f4 *q = reinterpret_cast<f4 *>(dst + t * 256);
+            const f4 v = lds[t * kWave + lane];
+            if (NT) __builtin_nontemporal_store(v, q); else *q = v;
+        }
+    }
+};
+
+template <class Op, class = void>
+struct LdsStaged {
+    static constexpr bool value = false;
+    static constexpr size_t bytes = 0;
+};
+template <class Op>
+struct LdsStaged<Op, std::void_t<decltype(Op::kLdsStaged)>> {
+    static constexpr bool value = Op::kLdsStaged;
+    static constexpr size_t bytes = Op::kLdsBytes;
+};
+
 // Momentum-SGD applied as the row arrives; the mix then averages the updated rows.
 // The whole chain runs in fp64 registers, in the order the formula is written:
 //     t = g + wd*x ;  v' = mu*v + t ;  h = x - lr*v' ;  x' = (h_i + h_peer) * 0.5
@@ -1123,6 +1184,18 @@ __global__ __launch_bounds__(kWave *kMaxWavesPerBlock) void gather_kernel(
         const int r = static_cast<int>(e & kOrderRowField);
         const int q = static_cast<int>((e >> kOrderRowBits) & kOrderRowField);
         if (r < n) row = r;
+        if constexpr (LdsStaged<Op>::value) {
+            // the whole chunk of this workgroup inside one segment and inside the row: every wavefront
+            // of the workgroup takes this branch together (the table entry and the chunk are shared)
+            const int64_t chunk_c0 = static_cast<int64_t>(chunk) * nwaves * kTileCols;
+            if ((e & kOrderOneSegment) != 0 && r < n && q < n && !skip_mix && U == 1 &&
+                nwaves * kWave == blockDim.x && static_cast<size_t>(nwaves) * nwaves * kWave * sizeof(f4) == LdsStaged<Op>::bytes &&
+                chunk_c0 + static_cast<int64_t>(nwaves) * kTileCols <= P) {
+                extern __shared__ f4 staging[];
+                op.template lds_mix<NT>(row, q, chunk_c0, lane, static_cast<int>(wave), staging);
+                return;
+            }
+        }
         if ((e & kOrderOneSegment) != 0 && r < n && q < n && c0 + kTileCols <= P) {
             op.template issue<U, true, false>(row, off, full_mask, mine);
             mix_and_store(std::true_type{}, full_mask, q);
@@ -1449,7 +1522,8 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     }
     int cap = cx_get_tuning(9);
     if (cap < 0 || cap > 16) cap = Op::kGather.wgs_per_cu;
-    const size_t glds = lds_reservation(cap);
+    size_t glds = lds_reservation(cap);
+    if (LdsStaged<Op>::value && glds < LdsStaged<Op>::bytes) glds = LdsStaged<Op>::bytes;
     if (nt)
         hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, glds, a.stream, op, a.n, a.P, a.S,
                            a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),

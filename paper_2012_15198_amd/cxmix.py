@@ -25,6 +25,7 @@ STATUS = {0: "CX_OK", -1: "CX_ERR_NULL", -2: "CX_ERR_SHAPE", -3: "CX_ERR_SEGMENT
 CX_TOPO_FAIR, CX_TOPO_DIRECTED_EXP, CX_TOPO_UNFAIR, CX_TOPO_SAME_ALL_SEGMENTS = 0, 1, 2, 16
 TUNE_SLICES, TUNE_WAVES, TUNE_NONTEMPORAL, TUNE_DEPTH = 0, 1, 2, 3
 TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE, TUNE_ORDERED, TUNE_WGS_PER_CU = 4, 5, 6, 7, 8, 9
+TUNE_LDS_MEAN = 10
 
 EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_segments",
            "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",

@@ -29,15 +29,15 @@ class Tuning:
     """Context manager: set the library's launch parameters, restore defaults after."""
 
     def __init__(self, slices=-1, waves=-1, nt=-1, depth=-1, lockstep=-1, force_walk=-1, cluster=-1,
-                 xcd_aware=-1, ordered=-1, wgs_per_cu=-1):
-        self.v = (slices, waves, nt, depth, lockstep, force_walk, cluster, xcd_aware, ordered, wgs_per_cu)
+                 xcd_aware=-1, ordered=-1, wgs_per_cu=-1, lds_mean=-1):
+        self.v = (slices, waves, nt, depth, lockstep, force_walk, cluster, xcd_aware, ordered, wgs_per_cu, lds_mean)
 
     def __enter__(self):
         for k, v in enumerate(self.v):
             cx.cx_set_tuning(k, v)
 
     def __exit__(self, *exc):
-        for k in range(10):
+        for k in range(11):
             cx.cx_set_tuning(k, -1)
 
 
@@ -52,7 +52,9 @@ ALL_TUNINGS = [(-1, -1, -1, -1), (1, 1, 0, 2), (2, 2, 1, 4), (4, 8, 0, 2), (1, 4
                (-1, -1, -1, -1, -1, -1, -1, -1, 1), (-1, -1, -1, -1, -1, 0, 1, 1, 1), (2, 8, 0, -1, -1, 0, 5, 0, 1),
                # in-place launches with a cap on resident workgroups per CU (last value)
                (1, 2, 1, 2, 1, 1, -1, -1, -1, 8), (2, 4, 1, 4, 0, 1, -1, -1, -1, 2), (4, 8, 0, 2, 1, 1, -1, -1, -1, 0),
-               (1, 3, 1, 4, 1, 1, -1, -1, -1, 16)]
+               (1, 3, 1, 4, 1, 1, -1, -1, -1, 16),
+               # the hierarchical mean staged through LDS (groups of 8, out of place, rows in cycle order)
+               (-1, -1, -1, -1, -1, -1, -1, -1, 1, -1, 1), (-1, -1, 0, -1, -1, 0, 2, 1, 1, 2, 1)]
 
 
 REL = 1e-6

@@ -10,7 +10,7 @@ import torch
 import oracle as O
 from paper_2012_15198_amd import cxmix as cx
 from paper_2012_15198_amd import workloads as WL
-from gpu_util import ALL_TUNINGS, Tuning, bits, dev, host, once, same_bits, within_rel, worst_rel
+from gpu_util import DEV, ALL_TUNINGS, Tuning, bits, dev, host, once, same_bits, within_rel, worst_rel
 
 pytestmark = pytest.mark.gpu
 
@@ -540,6 +540,28 @@ def test_hier_rounds_under_every_launch_shape(tuning):
             y0, y1 = y1, y0
         torch.cuda.synchronize()
     assert same_bits(host(xd), want)
+    assert same_bits(host(y0), want)
+
+
+@pytest.mark.parametrize("cluster", [1, 2, 5, -1])
+def test_hier_mean_staged_through_lds_gives_the_same_bits(cluster):
+    """Launch parameter 10: groups of 8 reduced through LDS (one row per wavefront).  Chunks wholly
+    inside a segment take that path, the others the register tree; every bit must equal the oracle's
+    fixed-order result either way.  Ragged end, a short first segment, and an empty one."""
+    W, G, P, ld, R = 64, 8, 150_001, 150_016, 3
+    so = np.array([0, 1500, 1500, 70_000, 110_000, P], dtype=np.int64)
+    x = WL.gen_matrix(W, P, 0.05, seed=33, ld=ld)
+    tabs = O.topology(33, W // G, len(so) - 1, 0, R)
+    want = x
+    for r in range(R):
+        want = O.hier_mix_f32(want, P, G, so, tabs[r])
+    with Tuning(ordered=1, cluster=cluster, lds_mean=1):
+        y0, y1 = dev(x), torch.full((W, ld), float("nan"), device=DEV)
+        y1[:, P:] = y0[:, P:]
+        for r in range(R):
+            cx.cx_hier_mix(y0, y1, P, G, dev(so), dev(tabs[r]))
+            y0, y1 = y1, y0
+        torch.cuda.synchronize()
     assert same_bits(host(y0), want)
 
 

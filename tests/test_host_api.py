@@ -221,7 +221,7 @@ def test_tuning_keys():
     for key, good, bad in [(cx.TUNE_SLICES, 2, 3), (cx.TUNE_WAVES, 8, 9), (cx.TUNE_NONTEMPORAL, 0, 2),
                            (cx.TUNE_DEPTH, 8, 3), (cx.TUNE_LOCKSTEP, 1, 2), (cx.TUNE_FORCE_WALK, 1, 2),
                            (cx.TUNE_CLUSTER, 64, 0), (cx.TUNE_XCD_AWARE, 0, 2), (cx.TUNE_ORDERED, 0, 2),
-                           (cx.TUNE_WGS_PER_CU, 4, 17)]:
+                           (cx.TUNE_WGS_PER_CU, 4, 17), (cx.TUNE_LDS_MEAN, 1, 2)]:
         cx.cx_set_tuning(key, good)
         assert cx.cx_get_tuning(key) == good
         with pytest.raises(cx.CxError):
@@ -229,7 +229,7 @@ def test_tuning_keys():
         cx.cx_set_tuning(key, -1)
         assert cx.cx_get_tuning(key) == -1
     with pytest.raises(cx.CxError):
-        cx.cx_set_tuning(10, 1)
+        cx.cx_set_tuning(11, 1)
 
 
 def test_header_is_plain_c_and_a_c_program_can_call_the_host_half(tmp_path):
