@@ -165,6 +165,30 @@ class Runner:
             "alg_bytes_per_launch": alg_bytes,
         }
 
+    def allocation_spread(self, count, steps):
+        """The same calls on `count` further allocations of the parameter matrix, the earlier ones kept
+        alive so that each lands on other physical pages: kernel time per allocation (median over `steps`
+        calls, events around each call).  Shows how much of a figure is placement, not code."""
+        torch = self.torch
+        held, out = [], []
+        alg = self.wl.W * self.wl.P * self.bytes_per_elem
+        for k in range(count):
+            if k:
+                held.append((self.x, self.y))
+                fresh = torch.empty_like(self.x).copy_(self.x)
+                self.y = fresh if self.in_place else torch.empty_like(self.x)
+                self.x = fresh
+            for _ in range(2):
+                self.step(False)
+            self.ev = []
+            for _ in range(steps):
+                self.step(True)
+            torch.cuda.synchronize()
+            t = float(np.median([a.elapsed_time(b) for a, b in self.ev]))
+            out.append({"address": hex(self.x.data_ptr()), "kernel_ms_median": t,
+                        "frac_of_hbm_peak": alg / (t * 1e-3) / 1e9 / HBM_PEAK_GBPS})
+        return out
+
     def whole_step_latency(self, rounds):
         """One step at a time, the device idle before and after: host clock around topology generation,
         table upload, launch and completion.  Median and minimum over `rounds` steps, in ms."""
@@ -375,6 +399,8 @@ def main():
     ap.add_argument("--f16", action="store_true", help="binary16 rows: cx_gossip_mix_f16 / cx_hier_mix_f16")
     ap.add_argument("--tune", default="", metavar="KEY=VALUE[,KEY=VALUE...]",
                     help="launch parameters for cx_set_tuning (see include/cx_mix.h), e.g. 6=8,1=4")
+    ap.add_argument("--allocations", type=int, default=0, metavar="K",
+                    help="also time the calls on K allocations of the matrix within this process (placement spread)")
     ap.add_argument("--in-place", action="store_true",
                     help="update the matrix in place (cycle-walk kernel) instead of ping-pong buffers")
     args = ap.parse_args()
@@ -401,7 +427,9 @@ def main():
     if rows16 and kind == "pushsum":
         sys.exit("bench.py: --bf16 / --f16 are not available for the push-sum comparison")
     latency_rounds = min(wl.rounds, 20)
-    runner = Runner(wl, kind, args.steps + args.warmup + latency_rounds, in_place=args.in_place, rows16=rows16)
+    spread_steps = min(args.steps, 8)
+    runner = Runner(wl, kind, args.steps + args.warmup + latency_rounds + args.allocations * (spread_steps + 2),
+                    in_place=args.in_place, rows16=rows16)
     res = runner.run(args.steps, args.warmup)
     traffic, traffic_source = profiled_traffic(wl.name, kind, args.in_place, rows16, tuning)
     out = {
@@ -430,6 +458,8 @@ def main():
     }
     out["whole_step_latency_ms"] = runner.whole_step_latency(latency_rounds)
     out["topology_gen"] = topology_gen_time(runner)
+    if args.allocations:
+        out["allocation_spread"] = runner.allocation_spread(args.allocations, spread_steps)
     if not args.no_copy:
         out["copy_ceiling"] = copy_ceiling(res["alg_bytes_per_launch"])
     del runner
