@@ -104,23 +104,12 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-// Column (relative to the tile's first) of element q of slice u in this lane: eight or four
-// consecutive columns per lane, or the 4 + 4 split of the operators that pair 16-bit and fp32 rows.
-template <class Op, class = void>
-struct SplitSlices {
-    static constexpr bool value = false;
-};
-template <class Op>
-struct SplitSlices<Op, std::void_t<decltype(Op::kSplit)>> {
-    static constexpr bool value = Op::kSplit;
-};
-
+// Column of element q of slice u in this lane: a lane owns kElems consecutive columns per slice.
 template <class Op>
 __device__ __forceinline__ int64_t column_of(int64_t c0, int lane, int u, int q)
 {
     constexpr int kSliceCols = Op::kElems;
-    if constexpr (SplitSlices<Op>::value) return c0 + u * (kWave * kSliceCols) + (q >> 2) * 256 + 4 * lane + (q & 3);
-    else return c0 + kSliceCols * lane + u * (kWave * kSliceCols) + q;
+    return c0 + kSliceCols * lane + u * (kWave * kSliceCols) + q;
 }
 
 // Orders LDS traffic between the lanes of ONE wavefront (wave-private LDS regions).
@@ -294,6 +283,24 @@ struct MeanLdsOp : MeanOp<G> {
         }
     }
 };
+
+// Operators that change between memory order and lane order through LDS say how much each wavefront
+// needs and are told where their areas start.
+template <class Op, class = void>
+struct StageBytes {
+    static constexpr int value = 0;
+};
+template <class Op>
+struct StageBytes<Op, std::void_t<decltype(Op::kStageBytes)>> {
+    static constexpr int value = Op::kStageBytes;
+};
+template <class Op>
+Op with_stage_base(const Op &op, size_t base)
+{
+    Op copy = op;
+    if constexpr (StageBytes<Op>::value > 0) copy.stage_base = static_cast<int>(base);
+    return copy;
+}
 
 template <class Op, class = void>
 struct LdsStaged {
@@ -599,26 +606,28 @@ __device__ __forceinline__ float to_f32_round_to_odd(double d)
     return __uint_as_float(bits);
 }
 
-// Column ownership of these operators ("split" slices): of every 512-column slice a lane owns
-// columns 4l..4l+3 and 256+4l..256+4l+3.  The 16-bit rows are then read with two 8-byte accesses
-// and the fp32 rows with two 16-byte ones, and every instruction of a wavefront covers one
-// contiguous 512-byte or 1-KB run.  (Eight consecutive columns per lane would suit the 16-bit rows
-// but leave each 16-byte access to the fp32 rows 32 bytes from its neighbour's: every cache line
-// requested twice, measured 7 % slower on the fused step.)  `p` = row base + tile start + 4*lane
-// (the kernels hand every operator the column of its lane's first element: column_of);
-// element e of slice u is column u*512 + (e/4)*256 + 4*lane + e%4 of the tile.
+// fp32 companion rows of 16-bit rows.  A lane owns 8 consecutive columns of a 512-column slice:
+// one 16-byte register of a 16-bit row, but TWO of an fp32 row, 32 bytes apart from the
+// neighbouring lane's -- read like that, every 16-byte access of a wavefront leaves half of each
+// cache line to the other access, and the fused step runs 7 % slower.  So whole slices of the
+// fp32 rows move between memory and registers in MEMORY order (register hh of lane l = columns
+// 256*hh + 4*l .. +3: each access of the wavefront one contiguous KB) and change to the lane's own
+// columns through 2 KB of LDS per wavefront (stage_to_own / stage_from_own).  Boundary tiles,
+// handled element by element, address the lane's own columns directly.
 template <int U, bool FULL, bool NT>
 __device__ __forceinline__ void tile_load8(const float *p, const unsigned (&mask)[U], Tile<2 * U> &t)
 {
+    // p = row base + this lane's first column (tile start + 8 * lane)
+    const int lane = static_cast<int>(threadIdx.x & (kWave - 1));
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-            const float *q = p + u * (kWave * 8) + 256 * hh;
             if constexpr (FULL) {
-                const f4 *q4 = reinterpret_cast<const f4 *>(q);
+                const f4 *q4 = reinterpret_cast<const f4 *>(p - 4 * lane + u * (kWave * 8) + 256 * hh);   // memory order
                 t.v[2 * u + hh] = NT ? __builtin_nontemporal_load(q4) : *q4;
             } else {
+                const float *q = p + u * (kWave * 8) + 4 * hh;                                           // own columns
 #pragma unroll
                 for (int e = 0; e < 4; ++e) t.v[2 * u + hh][e] = ((mask[u] >> (4 * hh + e)) & 1u) ? q[e] : 0.0f;
             }
@@ -628,15 +637,16 @@ __device__ __forceinline__ void tile_load8(const float *p, const unsigned (&mask
 template <int U, bool FULL, bool NT>
 __device__ __forceinline__ void tile_store8(float *p, const unsigned (&mask)[U], const Tile<2 * U> &t)
 {
+    const int lane = static_cast<int>(threadIdx.x & (kWave - 1));
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-            float *q = p + u * (kWave * 8) + 256 * hh;
             if constexpr (FULL) {
-                f4 *q4 = reinterpret_cast<f4 *>(q);
+                f4 *q4 = reinterpret_cast<f4 *>(p - 4 * lane + u * (kWave * 8) + 256 * hh);
                 if (NT) __builtin_nontemporal_store(t.v[2 * u + hh], q4); else *q4 = t.v[2 * u + hh];
             } else {
+                float *q = p + u * (kWave * 8) + 4 * hh;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     if ((mask[u] >> (4 * hh + e)) & 1u) q[e] = t.v[2 * u + hh][e];
@@ -644,55 +654,44 @@ __device__ __forceinline__ void tile_store8(float *p, const unsigned (&mask)[U],
         }
 }
 
-// the 16-bit rows in the same ownership: words 0, 1 of the register = the first four columns,
-// words 2, 3 = the second four
-template <int U, bool FULL, bool NT>
-__device__ __forceinline__ void tile_load16_split(const uint16_t *p, const unsigned (&mask)[U], Tile<U> &raw)
+// This wavefront's 2 KB of the workgroup's dynamic LDS, `stage_base` bytes in (the schedules of
+// the in-place kernel come first).
+constexpr int kStageBytesPerWave = 2048;
+__device__ __forceinline__ f4 *stage_of_this_wave(int stage_base)
 {
-    typedef unsigned u4 __attribute__((ext_vector_type(4)));
-    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    extern __shared__ f4 cx_dynamic_lds[];
+    return cx_dynamic_lds + (stage_base >> 4) + (threadIdx.x >> 6) * (kStageBytesPerWave / 16);
+}
+
+// registers in memory order -> the lane's own columns (register 0 = columns 8l..8l+3, 1 = 8l+4..8l+7)
+template <int U>
+__device__ __forceinline__ void stage_to_own(f4 *stage, Tile<2 * U> &t)
+{
+    const int lane = static_cast<int>(threadIdx.x & (kWave - 1));
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        u4 w = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            const uint16_t *q = p + u * (kWave * 8) + 256 * hh;
-            if constexpr (FULL) {
-                const u2 *q2 = reinterpret_cast<const u2 *>(q);
-                const u2 two = NT ? __builtin_nontemporal_load(q2) : *q2;
-                w[2 * hh] = two[0];
-                w[2 * hh + 1] = two[1];
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if ((mask[u] >> (4 * hh + e)) & 1u) w[2 * hh + (e >> 1)] |= static_cast<unsigned>(q[e]) << (16 * (e & 1));
-            }
-        }
-        raw.v[u] = __builtin_bit_cast(f4, w);
+        stage[lane] = t.v[2 * u];
+        stage[kWave + lane] = t.v[2 * u + 1];
+        wave_sync();
+        t.v[2 * u] = stage[2 * lane];
+        t.v[2 * u + 1] = stage[2 * lane + 1];
+        wave_sync();
     }
 }
 
-template <int U, bool FULL, bool NT>
-__device__ __forceinline__ void tile_store16_split(uint16_t *p, const unsigned (&mask)[U], const Tile<U> &raw)
+// and back, for the store
+template <int U>
+__device__ __forceinline__ void stage_from_own(f4 *stage, Tile<2 * U> &t)
 {
-    typedef unsigned u4 __attribute__((ext_vector_type(4)));
-    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const int lane = static_cast<int>(threadIdx.x & (kWave - 1));
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const u4 w = __builtin_bit_cast(u4, raw.v[u]);
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-            uint16_t *q = p + u * (kWave * 8) + 256 * hh;
-            if constexpr (FULL) {
-                u2 *q2 = reinterpret_cast<u2 *>(q);
-                const u2 two = {w[2 * hh], w[2 * hh + 1]};
-                if (NT) __builtin_nontemporal_store(two, q2); else *q2 = two;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if ((mask[u] >> (4 * hh + e)) & 1u) q[e] = static_cast<uint16_t>(w[2 * hh + (e >> 1)] >> (16 * (e & 1)));
-            }
-        }
+        stage[2 * lane] = t.v[2 * u];
+        stage[2 * lane + 1] = t.v[2 * u + 1];
+        wave_sync();
+        t.v[2 * u] = stage[lane];
+        t.v[2 * u + 1] = stage[kWave + lane];
+        wave_sync();
     }
 }
 
@@ -737,10 +736,10 @@ struct Fused16Op {
     static constexpr int kElems = 8;                       // 16-bit columns per 16-byte slice
     template <int U> using Work = WideTile<2 * U>;         // the updated row, 8 doubles per slice
     static constexpr int kRawPerSlice = 4;                 // x, g: one register each; v: two
-    static constexpr GatherShape kGather{1, 8, 192, 0};
+    static constexpr GatherShape kGather{1, 4, 192, 0};
     static constexpr WalkShape kWalk{1, 2, 4, 2};
     static constexpr int kMaxU = 1;
-    static constexpr bool kSplit = true;                   // lanes own 4 + 4 columns of a slice (see tile_load8)
+    static constexpr int kStageBytes = kStageBytesPerWave; // LDS per wavefront (see tile_load8)
     template <int U> struct Raw { Tile<U> x, g; Tile<2 * U> v; };
     const uint16_t *xin;
     uint16_t *xout;
@@ -749,29 +748,33 @@ struct Fused16Op {
     const uint16_t *g;
     int64_t ld;
     SgdStep sgd;
+    int stage_base = 0;   // bytes into the dynamic LDS where the wavefronts' staging areas start (set at launch)
 
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
     {
         const int64_t o = static_cast<int64_t>(row) * ld + off;
-        tile_load16_split<U, FULL, NT>(xin + o, mask, raw.x);
+        tile_load16<U, FULL, NT>(xin + o, mask, raw.x);
         tile_load8<U, FULL, NT>(vin + o, mask, raw.v);
-        tile_load16_split<U, FULL, NT>(g + o, mask, raw.g);
+        tile_load16<U, FULL, NT>(g + o, mask, raw.g);
     }
     template <int U, bool FULL, bool NT, bool COMMIT = true>
     __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
     {
-        Tile<2 * U> v32;
+        Tile<2 * U> v32 = raw.v;
+        if constexpr (FULL) stage_to_own<U>(stage_of_this_wave(stage_base), v32);     // memory order -> own columns
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
-                d4 v = widen(raw.v.v[2 * u + hh]);
+                d4 v = widen(v32.v[2 * u + hh]);
                 t.v[2 * u + hh] = sgd.apply(widen16_half<IEEE_HALF>(raw.x.v[u], hh), v, widen16_half<IEEE_HALF>(raw.g.v[u], hh));
                 v32.v[2 * u + hh] = narrow(v);
             }
-        if constexpr (COMMIT)
+        if constexpr (COMMIT) {
+            if constexpr (FULL) stage_from_own<U>(stage_of_this_wave(stage_base), v32);
             tile_store8<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
+        }
     }
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
@@ -779,7 +782,7 @@ struct Fused16Op {
         Tile<U> packed;
 #pragma unroll
         for (int u = 0; u < U; ++u) packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
-        tile_store16_split<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
+        tile_store16<U, FULL, NT>(xout + static_cast<int64_t>(row) * ld + off, mask, packed);
     }
 };
 
@@ -793,7 +796,7 @@ struct HierFused16Op {
         G == 1 ? GatherShape{1, 8, 192, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
     static constexpr WalkShape kWalk{1, 2, 2, 2};
     static constexpr int kMaxU = 1;
-    static constexpr bool kSplit = true;
+    static constexpr int kStageBytes = kStageBytesPerWave;
     template <int U> struct Raw { Tile<U> g[G], x; Tile<2 * U> v; };
     const uint16_t *xin;
     uint16_t *xout;
@@ -802,20 +805,22 @@ struct HierFused16Op {
     const uint16_t *g;    // [W][ld]
     int64_t ld;
     SgdStep sgd;
+    int stage_base = 0;   // as in Fused16Op
 
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
     {
         const int64_t lead = static_cast<int64_t>(row) * G * ld + off;
 #pragma unroll
-        for (int j = 0; j < G; ++j) tile_load16_split<U, FULL, NT>(g + lead + j * ld, mask, raw.g[j]);
-        tile_load16_split<U, FULL, NT>(xin + lead, mask, raw.x);
+        for (int j = 0; j < G; ++j) tile_load16<U, FULL, NT>(g + lead + j * ld, mask, raw.g[j]);
+        tile_load16<U, FULL, NT>(xin + lead, mask, raw.x);
         tile_load8<U, FULL, NT>(vin + static_cast<int64_t>(row) * ld + off, mask, raw.v);
     }
     template <int U, bool FULL, bool NT, bool COMMIT = true>
     __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
     {
-        Tile<2 * U> v32;
+        Tile<2 * U> v32 = raw.v;
+        if constexpr (FULL) stage_to_own<U>(stage_of_this_wave(stage_base), v32);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -824,12 +829,14 @@ struct HierFused16Op {
 #pragma unroll
                 for (int j = 0; j < G; ++j) gsum = gsum + widen16_half<IEEE_HALF>(raw.g[j].v[u], hh);
                 const d4 gbar = gsum / static_cast<double>(G);
-                d4 v = widen(raw.v.v[2 * u + hh]);
+                d4 v = widen(v32.v[2 * u + hh]);
                 t.v[2 * u + hh] = sgd.apply(widen16_half<IEEE_HALF>(raw.x.v[u], hh), v, gbar);
                 v32.v[2 * u + hh] = narrow(v);
             }
-        if constexpr (COMMIT)
+        if constexpr (COMMIT) {
+            if constexpr (FULL) stage_from_own<U>(stage_of_this_wave(stage_base), v32);
             tile_store8<U, FULL, NT>(vout + static_cast<int64_t>(row) * ld + off, mask, v32);
+        }
     }
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
@@ -839,7 +846,7 @@ struct HierFused16Op {
         for (int u = 0; u < U; ++u) packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
         uint16_t *p = xout + static_cast<int64_t>(row) * G * ld + off;
 #pragma unroll
-        for (int j = 0; j < G; ++j) tile_store16_split<U, FULL, NT>(p + j * ld, mask, packed);
+        for (int j = 0; j < G; ++j) tile_store16<U, FULL, NT>(p + j * ld, mask, packed);
     }
 };
 
@@ -1362,16 +1369,18 @@ bool try_launch(const Op &op, const Launch &l, const MixArgs &a)
         const int64_t tile_cols = static_cast<int64_t>(kWave) * Op::kElems * U;
         const int64_t ntiles = (a.P + tile_cols - 1) / tile_cols;
         int waves = l.waves;
-        while (waves > 1 && sizeof(int) * kScheduleWords(a.n) * waves > 48 * 1024) --waves;
+        while (waves > 1 && (sizeof(int) * kScheduleWords(a.n) + StageBytes<Op>::value) * waves > 48 * 1024) --waves;
         const int64_t nblocks = (ntiles + waves - 1) / waves;
         const dim3 grid(static_cast<unsigned>(nblocks)), block(kWave * waves);
-        size_t lds = sizeof(int) * kScheduleWords(a.n) * waves;
+        const size_t schedules = (sizeof(int) * kScheduleWords(a.n) * waves + 15) / 16 * 16;
+        size_t lds = schedules + static_cast<size_t>(StageBytes<Op>::value) * waves;
         if (lds < lds_reservation(l.wgs_per_cu)) lds = lds_reservation(l.wgs_per_cu);
+        const Op staged = with_stage_base(op, schedules);
         if (l.nt)
-            hipLaunchKernelGGL((mix_kernel<Op, U, D, true>), grid, block, lds, a.stream, op, a.n, a.P,
+            hipLaunchKernelGGL((mix_kernel<Op, U, D, true>), grid, block, lds, a.stream, staged, a.n, a.P,
                                a.S, a.seg_off, a.peers, a.shift, a.skip_mix, ntiles, l.lockstep);
         else
-            hipLaunchKernelGGL((mix_kernel<Op, U, D, false>), grid, block, lds, a.stream, op, a.n, a.P,
+            hipLaunchKernelGGL((mix_kernel<Op, U, D, false>), grid, block, lds, a.stream, staged, a.n, a.P,
                                a.S, a.seg_off, a.peers, a.shift, a.skip_mix, ntiles, l.lockstep);
         return true;
     }
@@ -1524,12 +1533,14 @@ bool try_gather(const Op &op, int want_u, int waves, int nt, int cl_req, int xcd
     if (cap < 0 || cap > 16) cap = Op::kGather.wgs_per_cu;
     size_t glds = lds_reservation(cap);
     if (LdsStaged<Op>::value && glds < LdsStaged<Op>::bytes) glds = LdsStaged<Op>::bytes;
+    if (glds < static_cast<size_t>(StageBytes<Op>::value) * waves) glds = static_cast<size_t>(StageBytes<Op>::value) * waves;
+    const Op staged = with_stage_base(op, 0);
     if (nt)
-        hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, glds, a.stream, op, a.n, a.P, a.S,
+        hipLaunchKernelGGL((gather_kernel<Op, U, true>), grid, block, glds, a.stream, staged, a.n, a.P, a.S,
                            a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),
                            static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, order);
     else
-        hipLaunchKernelGGL((gather_kernel<Op, U, false>), grid, block, glds, a.stream, op, a.n, a.P, a.S,
+        hipLaunchKernelGGL((gather_kernel<Op, U, false>), grid, block, glds, a.stream, staged, a.n, a.P, a.S,
                            a.seg_off, a.peers, a.shift, a.skip_mix, static_cast<unsigned>(nchunks),
                            static_cast<unsigned>(cl), static_cast<unsigned>(waves), xcd_shift, order);
     *status = hipGetLastError() == hipSuccess ? CX_OK : CX_ERR_HIP;
