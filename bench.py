@@ -303,10 +303,10 @@ def cpu_baseline(wl, kind, rows16=None, budget_s=12.0, max_bytes=8 << 30):
     narrow = {None: lambda a: a, "bf16": lambda a: (a.view(np.uint32) >> 16).astype(np.uint16),
               "f16": lambda a: a.astype(np.float16).view(np.uint16)}[fmt]       # input preparation only
     tabs = O.topology(wl.seed, n, S, 0, 16, 1 if kind == "pushsum" else 0)
-    name = {"gossip": "oracle_gossip_mix", "hier": "oracle_hier_mix_f32", "pushsum": "oracle_pushsum_mix_f32",
+    name = {"gossip": "oracle_gossip_mix", "hier": "oracle_hier_mix_f64", "pushsum": "oracle_pushsum_mix_f32",
             "fused": "oracle_sgd_fused_mix_f64", "hiersgd": "oracle_hier_sgd_fused_mix_f64"}[kind]
     if fmt:
-        name = {"gossip": f"oracle_gossip_mix_{fmt}", "hier": "oracle_hier_mix16_f32", "fused": "oracle_sgd_fused_mix16",
+        name = {"gossip": f"oracle_gossip_mix_{fmt}", "hier": "oracle_hier_mix16", "fused": "oracle_sgd_fused_mix16",
                 "hiersgd": "oracle_hier_sgd_fused_mix16"}[kind]
     x = v = g = so = spare = None
     w = np.ones(wl.W, dtype=np.float32)
@@ -333,7 +333,7 @@ def cpu_baseline(wl, kind, rows16=None, budget_s=12.0, max_bytes=8 << 30):
         elif kind == "gossip":
             x = (O.gossip_mix_bf16 if fmt == "bf16" else O.gossip_mix_f16)(x, P, so, t)
         elif kind == "hier":
-            x = O.hier_mix_f32(x, P, wl.G, so, t) if not fmt else O.hier_mix16_f32(fmt, x, P, wl.G, so, t)
+            x = O.hier_mix_f64(x, P, wl.G, so, t).astype(np.float32) if not fmt else O.hier_mix16(fmt, x, P, wl.G, so, t)
         elif kind == "pushsum":
             x, w, _ = O.pushsum_mix_f32(x, w, P, int((0 - int(t[0, 0])) % wl.W), False)
         elif kind == "fused":

@@ -183,10 +183,12 @@ int cx_gossip_mix_noalloc(const float *x_in, float *x_out, int64_t ld, int32_t W
 /* ------------------------------------------------------------------------------------
  * cx_hier_mix -- hierarchical Crossover-SGD (Section 3.3) on parameters: groups are G
  * consecutive rows, the first row of a group is its leader, L = W / G.
- *     m_g  = (pairwise-tree fp32 sum of the G rows of group g) * (1.0f / G)
- *     y_g  = (m_g + m_{leader_peers[s][g]}) * 0.5f          (skipped when L == 1)
- *     every row of group g  <-  y_g
- * The tree splits a run of k rows at the largest power of two below k.
+ *     m_g  = (x_{gG} + x_{gG+1} + ... + x_{gG+G-1}) / G        (rows summed in order)
+ *     y_g  = (m_g + m_{leader_peers[s][g]}) * 0.5              (skipped when L == 1)
+ *     every row of group g  <-  fp32(y_g)
+ * evaluated in fp64 (inputs widened exactly) and rounded ONCE to fp32, nearest even: the result is
+ * the correctly rounded value of the formula, within 2^-24 relative of it however much cancels
+ * inside a group.  G == 1 is cx_gossip_mix (its fp32 formula, bit for bit).
  * leader_peers_dev is int32 [S][L] (may be NULL when L == 1: the result is then the
  * global mean, i.e. the AllReduce mixing matrix).
  * Errors: as cx_gossip_mix, plus CX_ERR_SHAPE if G < 1, W % G != 0 or L > CX_MAX_ROWS;
@@ -277,11 +279,11 @@ int cx_gossip_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t
 
 /* ------------------------------------------------------------------------------------
  * cx_hier_mix_bf16 / cx_hier_mix_f16 -- cx_hier_mix (Section 3.3) on 16-bit rows: x is uint16
- * [W][ld] of bfloat16 / binary16 bit patterns, ld % 8 == 0.  Every value is widened exactly,
- * the group sum (fixed pairwise tree), the scaling by 1/G and the leader average run in fp32 as
- * in cx_hier_mix, and the result is rounded ONCE (nearest even) before it is written to the G
- * rows of the group.  G = 1, 2, 4, 8 (CX_ERR_UNSUPPORTED otherwise); G = 1 is
- * cx_gossip_mix_bf16 / _f16 (and needs W >= 2).  Everything else as cx_hier_mix.
+ * [W][ld] of bfloat16 / binary16 bit patterns, ld % 8 == 0.  Every value is widened exactly, the
+ * group sum, the division by G and the leader average run in fp64 as in cx_hier_mix, and the result
+ * is rounded ONCE (nearest even, straight from the fp64 value) before it is written to the G rows of
+ * the group.  G = 1, 2, 4, 8 (CX_ERR_UNSUPPORTED otherwise); G = 1 is cx_gossip_mix_bf16 / _f16 (and
+ * needs W >= 2).  Everything else as cx_hier_mix.
  */
 int cx_hier_mix_bf16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int64_t P,
                      int32_t G, int32_t S, const int64_t *seg_off_dev,

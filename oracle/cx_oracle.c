@@ -598,6 +598,29 @@ uint16_t oracle_f64_to_f16(double d) { return round_double_to_16(d, 10, -14, 15,
 
 static uint16_t narrow16_from_double(int fmt, double d) { return fmt ? oracle_f64_to_f16(d) : oracle_f64_to_bf16(d); }
 
+/* n doubles -> n 16-bit patterns, each rounded once (the loop over the function above). */
+void oracle_narrow16_array(int fmt, const double *in, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = narrow16_from_double(fmt, in[i]);
+}
+
+/* The hierarchical step on 16-bit rows with ONE rounding: oracle_hier_mix16_f64's doubles, each
+ * rounded straight to the 16-bit format (the variant above rounds an fp32 tree sum instead). */
+int oracle_hier_mix16(int fmt, const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W,
+                      int64_t P, int32_t G, int32_t S, const int64_t *seg_off,
+                      const int32_t *leader_peers)
+{
+    size_t n = (size_t)W * (size_t)ld;
+    double *y = (double *)calloc(n, sizeof(double));
+    if (!y) return -2;
+    int rc = oracle_hier_mix16_f64(fmt, x_in, y, ld, W, P, G, S, seg_off, leader_peers);
+    for (int32_t s = 0; rc == 0 && s < S; ++s)
+        for (int64_t c = seg_off[s]; c < seg_off[s + 1]; ++c)
+            for (int32_t i = 0; i < W; ++i) x_out[i * ld + c] = narrow16_from_double(fmt, y[i * ld + c]);
+    free(y);
+    return rc;
+}
+
 /* Reference mode: the unrounded doubles.  x, g: uint16 [W][ld]; v: float [W][ld]. */
 int oracle_sgd_fused_mix16_f64(int fmt, const uint16_t *x_in, const float *v_in, const uint16_t *g,
                                double *x_out, double *v_out, float lr, float mu, float wd,

@@ -25,7 +25,7 @@ __all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topo
            "hier_sgd_fused_mix_f64", "hier_sgd_fused_mix_f32", "gossip_mix_bf16", "f32_to_bf16",
            "bf16_to_f32", "gossip_mix_f16", "f32_to_f16", "f16_to_f32", "hier_mix16_f64", "hier_mix16_f32",
            "f64_to_bf16", "f64_to_f16", "sgd_fused_mix16_f64", "sgd_fused_mix16",
-           "hier_sgd_fused_mix16_f64", "hier_sgd_fused_mix16"]
+           "hier_sgd_fused_mix16_f64", "hier_sgd_fused_mix16", "narrow16", "hier_mix16"]
 
 
 def build_oracle(force: bool = False) -> str:
@@ -84,6 +84,9 @@ def _L():
             fn.argtypes = [i32, vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, vp, vp]
         for fn in (lib.oracle_hier_sgd_fused_mix16_f64, lib.oracle_hier_sgd_fused_mix16):
             fn.argtypes = [i32, vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32, vp, vp]
+        lib.oracle_narrow16_array.restype = None
+        lib.oracle_narrow16_array.argtypes = [i32, vp, vp, i64]
+        lib.oracle_hier_mix16.argtypes = [i32, vp, vp, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_pushsum_mix_f64.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
         lib.oracle_pushsum_mix_f32.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
         _lib = lib
@@ -389,3 +392,17 @@ def hier_sgd_fused_mix16_f64(fmt, x, v, g, lr, mu, wd, P, G, seg_off, leader_pee
 
 def hier_sgd_fused_mix16(fmt, x, v, g, lr, mu, wd, P, G, seg_off, leader_peers):
     return _fused16(_L().oracle_hier_sgd_fused_mix16, False, fmt, x, v, g, lr, mu, wd, P, seg_off, leader_peers, G)
+
+
+def narrow16(fmt, a) -> np.ndarray:
+    """Doubles -> 16-bit patterns ("bf16" / "f16"), each rounded once; the array form of f64_to_bf16 / f64_to_f16."""
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    out = np.empty(a.shape, dtype=np.uint16)
+    _L().oracle_narrow16_array(_FMT[fmt], _p(a), _p(out), a.size)
+    return out
+
+
+def hier_mix16(fmt, x, P, G, seg_off, leader_peers) -> np.ndarray:
+    """The hierarchical step on 16-bit rows in double with ONE rounding to the 16-bit format: uint16 [W][ld]."""
+    x = _mat(x, dtype=np.uint16)
+    return _hier16(_L().oracle_hier_mix16, fmt, x, x.copy(), P, G, seg_off, leader_peers)

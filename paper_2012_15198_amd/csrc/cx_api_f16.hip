@@ -11,7 +11,7 @@ int cx_gossip_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t
     if (W < 2 || W > CX_MAX_ROWS) return (!x_in || !x_out) ? CX_ERR_NULL : CX_ERR_SHAPE;
     const int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags, 2);
     if (rc != CX_OK) return rc;
-    const Fp16Op op{x_in, x_out, ld, 1.0f};
+    const Fp16Op op{x_in, x_out, ld};
     const MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream), x_in != x_out, 1};
     return launch_mix<Fp16Op>(op, a);
 }

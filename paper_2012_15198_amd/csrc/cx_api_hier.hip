@@ -15,20 +15,19 @@ int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t 
     const int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
     if (rc != CX_OK) return rc;
     const hipStream_t st = static_cast<hipStream_t>(stream);
-    const float inv_g = 1.0f / static_cast<float>(G);
     const int skip = (L == 1) ? 1 : 0;
     const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
     const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
     switch (G) {
-    case 1: return launch_mix<MeanOp<1>>(MeanOp<1>{x_in, x_out, ld, inv_g}, a);
-    case 2: return launch_mix<MeanOp<2>>(MeanOp<2>{x_in, x_out, ld, inv_g}, a);
-    case 4: return launch_mix<MeanOp<4>>(MeanOp<4>{x_in, x_out, ld, inv_g}, a);
+    case 1: return launch_mix<MeanOp<1>>(MeanOp<1>{x_in, x_out, ld}, a);
+    case 2: return launch_mix<MeanOp<2>>(MeanOp<2>{x_in, x_out, ld}, a);
+    case 4: return launch_mix<MeanOp<4>>(MeanOp<4>{x_in, x_out, ld}, a);
     case 8:
         // launch parameter 10: the group mean staged through LDS (one row per wavefront) instead of the
         // register tree -- same results, kept so that the two can be measured side by side
-        if (cx_get_tuning(10) == 1) return launch_mix<MeanLdsOp<8>>(MeanLdsOp<8>{{x_in, x_out, ld, inv_g}}, a);
-        return launch_mix<MeanOp<8>>(MeanOp<8>{x_in, x_out, ld, inv_g}, a);
-    case 16: return launch_mix<MeanOp<16>>(MeanOp<16>{x_in, x_out, ld, inv_g}, a);
+        if (cx_get_tuning(10) == 1) return launch_mix<MeanLdsOp<8>>(MeanLdsOp<8>{{x_in, x_out, ld}}, a);
+        return launch_mix<MeanOp<8>>(MeanOp<8>{x_in, x_out, ld}, a);
+    case 16: return launch_mix<MeanOp<16>>(MeanOp<16>{x_in, x_out, ld}, a);
     default: return CX_ERR_UNSUPPORTED;
     }
 }

@@ -20,14 +20,13 @@ int hier_mix16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int
     const int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags, 2);
     if (rc != CX_OK) return rc;
     const hipStream_t st = static_cast<hipStream_t>(stream);
-    const float inv_g = 1.0f / static_cast<float>(G);
     const int skip = (L == 1) ? 1 : 0;
     const int32_t *peers = (L == 1) ? nullptr : leader_peers_dev;
     const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
     switch (G) {
-    case 2: return launch_mix<Row16Op<IEEE_HALF, 2>>(Row16Op<IEEE_HALF, 2>{x_in, x_out, ld, inv_g}, a);
-    case 4: return launch_mix<Row16Op<IEEE_HALF, 4>>(Row16Op<IEEE_HALF, 4>{x_in, x_out, ld, inv_g}, a);
-    case 8: return launch_mix<Row16Op<IEEE_HALF, 8>>(Row16Op<IEEE_HALF, 8>{x_in, x_out, ld, inv_g}, a);
+    case 2: return launch_mix<Row16Op<IEEE_HALF, 2>>(Row16Op<IEEE_HALF, 2>{x_in, x_out, ld}, a);
+    case 4: return launch_mix<Row16Op<IEEE_HALF, 4>>(Row16Op<IEEE_HALF, 4>{x_in, x_out, ld}, a);
+    case 8: return launch_mix<Row16Op<IEEE_HALF, 8>>(Row16Op<IEEE_HALF, 8>{x_in, x_out, ld}, a);
     default: return CX_ERR_UNSUPPORTED;
     }
 }

@@ -41,7 +41,7 @@ int cx_gossip_mix_noalloc(const float *x_in, float *x_out, int64_t ld, int32_t W
     const int rc = check_matrix_args(x_in, x_out, ld, W, P, S, flags);
     if (rc != CX_OK) return rc;
     if (x_in == x_out) return CX_ERR_ALIAS;          // the in-place kernel has no scratch to place
-    const MeanOp<1> op{x_in, x_out, ld, 1.0f};
+    const MeanOp<1> op{x_in, x_out, ld};
     MixArgs a{W, P, S, seg_off_dev, peers_dev, 0, 0, static_cast<hipStream_t>(stream), true, 1};
     a.order_provider = scratch_on_current_device;
     a.order_entries = CX_NOALLOC_ORDER_WORDS;

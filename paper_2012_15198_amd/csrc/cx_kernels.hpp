@@ -91,6 +91,8 @@ struct WideTile {
 // Algorithm 1's averaging line on one vector of columns, in the precision of the tile.
 __device__ __forceinline__ f4 average(const f4 &a, const f4 &b) { return (a + b) * 0.5f; }
 __device__ __forceinline__ d4 average(const d4 &a, const d4 &b) { return (a + b) * 0.5; }
+__device__ __forceinline__ d4 widen(const f4 &a) { return __builtin_convertvector(a, d4); }   // exact
+__device__ __forceinline__ f4 narrow(const d4 &a) { return __builtin_convertvector(a, f4); }  // one rounding, nearest even
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -156,24 +158,6 @@ __device__ __forceinline__ void tile_store(float *p, const unsigned (&mask)[U], 
     }
 }
 
-// Pairwise tree over N tiles: split at the largest power of two below N.
-template <int N, int U>
-__device__ __forceinline__ Tile<U> tree_sum(const Tile<U> *r)
-{
-    if constexpr (N == 1) {
-        return r[0];
-    } else {
-        constexpr int H = (N > 16) ? 16 : (N > 8) ? 8 : (N > 4) ? 4 : (N > 2) ? 2 : 1;
-        static_assert(N <= 32, "group size");
-        const Tile<U> a = tree_sum<H, U>(r);
-        const Tile<U> b = tree_sum<N - H, U>(r + H);
-        Tile<U> s;
-#pragma unroll
-        for (int u = 0; u < U; ++u) s.v[u] = a.v[u] + b.v[u];
-        return s;
-    }
-}
-
 // ---------------------------------------------------------------------------------
 // Row operators: what "load gossiping row r" and "store gossiping row r" mean.
 // ---------------------------------------------------------------------------------
@@ -190,10 +174,15 @@ struct WalkShape {
 };                                     // resident workgroups per CU (0 = as many as fit)
 
 // Plain gossip (G == 1) and hierarchical mode (a gossiping row = a group of G rows).
+// G == 1 is Algorithm 1's averaging line in fp32, as written.  For G > 1 the group sum (rows in
+// order, from zero), the division by G and the average between leaders run in fp64 registers and
+// the result is rounded ONCE to fp32: the correctly rounded value of the plain definition, whatever
+// cancels inside the group -- an fp32 sum of values that cancel cannot promise an error relative to
+// the result.  The kernel is bound by HBM bandwidth; the fp64 rate is not what limits it.
 template <int G>
 struct MeanOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
-    template <int U> using Work = Tile<U>;                 // fp32 values a lane works on
+    template <int U> using Work = std::conditional_t<G == 1, Tile<U>, WideTile<U>>;
     static constexpr int kRawPerSlice = G;
     // out-of-place launch: slices per lane, waves per workgroup, KB of one visit to a gossiping row
     // (all G rows behind it) per XCD -- measured optima on MI355X
@@ -205,7 +194,6 @@ struct MeanOp {
     const float *xin;
     float *xout;
     int64_t ld;
-    float inv_g;
 
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
@@ -215,30 +203,41 @@ struct MeanOp {
         for (int j = 0; j < G; ++j) tile_load<U, FULL, NT>(p + j * ld, mask, raw.r[j]);
     }
     template <int U, bool FULL, bool NT, bool COMMIT = true>
-    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Tile<U> &t) const
+    __device__ __forceinline__ void finish(int row, int64_t off, const unsigned (&mask)[U], const Raw<U> &raw, Work<U> &t) const
     {
         if constexpr (G == 1) {
             t = raw.r[0];
         } else {
-            t = tree_sum<G, U>(raw.r);
 #pragma unroll
-            for (int u = 0; u < U; ++u) t.v[u] = t.v[u] * inv_g;
+            for (int u = 0; u < U; ++u) {
+                d4 sum = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int j = 0; j < G; ++j) sum = sum + widen(raw.r[j].v[u]);
+                t.v[u] = sum / static_cast<double>(G);
+            }
         }
     }
     template <int U, bool FULL, bool NT>
-    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Tile<U> &t) const
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
     {
+        Tile<U> out;
+        if constexpr (G == 1) {
+            out = t;
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) out.v[u] = narrow(t.v[u]);
+        }
         float *p = xout + static_cast<int64_t>(row) * G * ld + off;
 #pragma unroll
-        for (int j = 0; j < G; ++j) tile_store<U, FULL, NT>(p + j * ld, mask, t);
+        for (int j = 0; j < G; ++j) tile_store<U, FULL, NT>(p + j * ld, mask, out);
     }
 };
 
 // The hierarchical mean staged through LDS, kept for measurement next to the register tree (launch
 // parameter 10).  A workgroup is G wavefronts and owns G tiles of 256 columns; wavefront j fetches
 // row j of its group and of the partner group (G contiguous 1-KB loads each), the rows meet in
-// LDS (G x G KB), wavefront w reduces tile w over the G rows with the same pairwise tree, and the
-// result travels back through LDS so that wavefront j stores row j.  Same arithmetic in the
+// LDS (G x G KB), wavefront w reduces tile w over the G rows in the same order and precision, and
+// the result travels back through LDS so that wavefront j stores row j.  Same arithmetic in the
 // same order as MeanOp<G>, hence the same bits; five barriers per workgroup.  Chunks that a
 // segment boundary or the row end crosses take MeanOp<G>'s register path.
 template <int G>
@@ -257,22 +256,23 @@ struct MeanLdsOp : MeanOp<G> {
         for (int t = 0; t < G; ++t) mine[t] = *reinterpret_cast<const f4 *>(own + t * 256);
 #pragma unroll
         for (int t = 0; t < G; ++t) theirs[t] = *reinterpret_cast<const f4 *>(oth + t * 256);
-        Tile<1> r[G];
 #pragma unroll
         for (int t = 0; t < G; ++t) lds[(wave * G + t) * kWave + lane] = mine[t];        // [row][tile][lane]
         __syncthreads();
+        d4 a = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int j = 0; j < G; ++j) r[j].v[0] = lds[(j * G + wave) * kWave + lane];
-        const f4 a = tree_sum<G, 1>(r).v[0] * this->inv_g;
+        for (int j = 0; j < G; ++j) a = a + widen(lds[(j * G + wave) * kWave + lane]);
+        a = a / static_cast<double>(G);
         __syncthreads();
 #pragma unroll
         for (int t = 0; t < G; ++t) lds[(wave * G + t) * kWave + lane] = theirs[t];
         __syncthreads();
+        d4 c = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-        for (int j = 0; j < G; ++j) r[j].v[0] = lds[(j * G + wave) * kWave + lane];
-        const f4 c = tree_sum<G, 1>(r).v[0] * this->inv_g;
+        for (int j = 0; j < G; ++j) c = c + widen(lds[(j * G + wave) * kWave + lane]);
+        c = c / static_cast<double>(G);
         __syncthreads();
-        lds[wave * kWave + lane] = average(a, c);                                        // result tile `wave`
+        lds[wave * kWave + lane] = narrow(average(a, c));                                        // result tile `wave`
         __syncthreads();
         float *dst = this->xout + (static_cast<int64_t>(row) * G + wave) * this->ld + col;
 #pragma unroll
@@ -321,8 +321,6 @@ struct LdsStaged<Op, std::void_t<decltype(Op::kLdsStaged)>> {
 // fp32 chain would round six times against intermediates larger than the result and misses a
 // 1e-6 relative bound once the momentum has grown; the kernel is bound by HBM bandwidth, so
 // the fp64 rate is not what limits it.
-__device__ __forceinline__ d4 widen(const f4 &a) { return __builtin_convertvector(a, d4); }
-__device__ __forceinline__ f4 narrow(const d4 &a) { return __builtin_convertvector(a, f4); }
 
 struct SgdStep {
     double lr, mu, wd;
@@ -490,13 +488,63 @@ __device__ __forceinline__ void tile_store16(uint16_t *p, const unsigned (&mask)
     }
 }
 
-// G == 1: plain gossip on 16-bit rows.  G > 1: hierarchical mode, a gossiping row = a group of
-// G rows whose widened values are tree-summed in fp32, scaled by 1/G, averaged between leaders
-// and rounded once on the way out.
+// double -> fp32 with rounding to odd: the discarded bits survive as a sticky last bit, so that the
+// hardware's round-to-nearest-even conversion to 16 bits that follows is ONE rounding of the double.
+__device__ __forceinline__ float to_f32_round_to_odd(double d)
+{
+    const float f = static_cast<float>(d);                 // nearest even
+    const double back = static_cast<double>(f);
+    unsigned bits = __float_as_uint(f);
+    if (back != d && d == d) {                             // inexact (and not a NaN)
+        if (__builtin_fabs(back) > __builtin_fabs(d)) bits -= 1;   // step back to the truncated value
+        bits |= 1u;                                        // and remember that something was cut off
+    }
+    return __uint_as_float(bits);
+}
+
+// half hh (words 2*hh, 2*hh+1) of a packed 16-bit slice, widened exactly to doubles
+template <bool IEEE_HALF>
+__device__ __forceinline__ d4 widen16_half(const f4 &packed, int hh)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    const u4 w = __builtin_bit_cast(u4, packed);
+    d4 out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const unsigned pair = hh == 0 ? w[e >> 1] : w[2 + (e >> 1)];
+        const unsigned h = (pair >> (16 * (e & 1))) & 0xffffu;
+        out[e] = static_cast<double>(IEEE_HALF ? f16_bits_to_float(h) : bf16_bits_to_float(h));
+    }
+    return out;
+}
+
+// eight doubles -> one packed 16-bit slice, each rounded once (nearest even)
+template <bool IEEE_HALF>
+__device__ __forceinline__ f4 narrow16_once(const d4 &lo, const d4 &hi)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    u4 w;
+#pragma unroll
+    for (int pair = 0; pair < 4; ++pair) {
+        const d4 &src = pair < 2 ? lo : hi;
+        const f2 two = {to_f32_round_to_odd(src[2 * (pair & 1)]), to_f32_round_to_odd(src[2 * (pair & 1) + 1])};
+        if constexpr (IEEE_HALF) w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, h2));
+        else w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
+    }
+    return __builtin_bit_cast(f4, w);
+}
+
+// G == 1: plain gossip on 16-bit rows: widen, add and halve in fp32, round once.  G > 1: hierarchical
+// mode, a gossiping row = a group of G rows whose widened values are summed (rows in order), divided
+// by G and averaged between leaders in fp64 registers, as in MeanOp<G>, and rounded ONCE to the 16-bit
+// format on the way out.
 template <bool IEEE_HALF, int G = 1>
 struct Row16Op {
     static constexpr int kElems = 8;                       // 16-bit columns per 16-byte slice
-    template <int U> using Work = Tile<2 * U>;             // 8 fp32 values per slice
+    template <int U> using Work = std::conditional_t<G == 1, Tile<2 * U>, WideTile<2 * U>>;   // 8 values per slice
     static constexpr int kRawPerSlice = G;
     static constexpr GatherShape kGather =
         G == 1 ? GatherShape{1, 8, 128, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
@@ -506,7 +554,6 @@ struct Row16Op {
     const uint16_t *xin;
     uint16_t *xout;
     int64_t ld;
-    float inv_g;
 
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void issue(int row, int64_t off, const unsigned (&mask)[U], Raw<U> &raw) const
@@ -516,7 +563,7 @@ struct Row16Op {
         for (int j = 0; j < G; ++j) tile_load16<U, FULL, NT>(p + j * ld, mask, raw.r[j]);
     }
     template <int U>
-    static __device__ __forceinline__ void widen(const Tile<U> &packed, Work<U> &t)
+    static __device__ __forceinline__ void widen(const Tile<U> &packed, Tile<2 * U> &t)
     {
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
 #pragma unroll
@@ -535,27 +582,16 @@ struct Row16Op {
         if constexpr (G == 1) {
             widen<U>(raw.r[0], t);
         } else {
-            t = widened_tree_sum<G, U>(raw.r);
 #pragma unroll
-            for (int u = 0; u < 2 * U; ++u) t.v[u] = t.v[u] * inv_g;
-        }
-    }
-    // tree_sum's order (split at the largest power of two below N) with the leaves widened on
-    // demand, so only one partial sum per tree level is alive at a time.
-    template <int N, int U>
-    static __device__ __forceinline__ Work<U> widened_tree_sum(const Tile<U> *r)
-    {
-        Work<U> s;
-        if constexpr (N == 1) {
-            widen<U>(r[0], s);
-        } else {
-            constexpr int H = (N > 16) ? 16 : (N > 8) ? 8 : (N > 4) ? 4 : (N > 2) ? 2 : 1;
-            const Work<U> a = widened_tree_sum<H, U>(r);
-            const Work<U> b = widened_tree_sum<N - H, U>(r + H);
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int u = 0; u < 2 * U; ++u) s.v[u] = a.v[u] + b.v[u];
+                for (int hh = 0; hh < 2; ++hh) {
+                    d4 sum = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                    for (int j = 0; j < G; ++j) sum = sum + widen16_half<IEEE_HALF>(raw.r[j].v[u], hh);
+                    t.v[2 * u + hh] = sum / static_cast<double>(G);
+                }
         }
-        return s;
     }
     template <int U, bool FULL, bool NT>
     __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
@@ -567,15 +603,19 @@ struct Row16Op {
         Tile<U> packed;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            u4 w;
+            if constexpr (G == 1) {
+                u4 w;
 #pragma unroll
-            for (int pair = 0; pair < 4; ++pair) {
-                // two fp32 -> one packed 16-bit pair, round-to-nearest-even in hardware
-                const f2 two = {t.v[2 * u + (pair >> 1)][2 * (pair & 1)], t.v[2 * u + (pair >> 1)][2 * (pair & 1) + 1]};
-                if constexpr (IEEE_HALF) w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, h2));
-                else w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
+                for (int pair = 0; pair < 4; ++pair) {
+                    // two fp32 -> one packed 16-bit pair, round-to-nearest-even in hardware
+                    const f2 two = {t.v[2 * u + (pair >> 1)][2 * (pair & 1)], t.v[2 * u + (pair >> 1)][2 * (pair & 1) + 1]};
+                    if constexpr (IEEE_HALF) w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, h2));
+                    else w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
+                }
+                packed.v[u] = __builtin_bit_cast(f4, w);
+            } else {
+                packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
             }
-            packed.v[u] = __builtin_bit_cast(f4, w);
         }
         uint16_t *p = xout + static_cast<int64_t>(row) * G * ld + off;
 #pragma unroll
@@ -594,18 +634,6 @@ using Fp16Op = Row16Op<true>;
 // odd (the discarded bits survive as a sticky last bit), which makes the hardware's
 // round-to-nearest-even conversion to 16 bits equal to one rounding of the double itself.
 // ---------------------------------------------------------------------------------
-__device__ __forceinline__ float to_f32_round_to_odd(double d)
-{
-    const float f = static_cast<float>(d);                 // nearest even
-    const double back = static_cast<double>(f);
-    unsigned bits = __float_as_uint(f);
-    if (back != d && d == d) {                             // inexact (and not a NaN)
-        if (__builtin_fabs(back) > __builtin_fabs(d)) bits -= 1;   // step back to the truncated value
-        bits |= 1u;                                        // and remember that something was cut off
-    }
-    return __uint_as_float(bits);
-}
-
 // fp32 companion rows of 16-bit rows.  A lane owns 8 consecutive columns of a 512-column slice:
 // one 16-byte register of a 16-bit row, but TWO of an fp32 row, 32 bytes apart from the
 // neighbouring lane's -- read like that, every 16-byte access of a wavefront leaves half of each
@@ -693,41 +721,6 @@ __device__ __forceinline__ void stage_from_own(f4 *stage, Tile<2 * U> &t)
         t.v[2 * u + 1] = stage[kWave + lane];
         wave_sync();
     }
-}
-
-// half hh (words 2*hh, 2*hh+1) of a packed 16-bit slice, widened exactly to doubles
-template <bool IEEE_HALF>
-__device__ __forceinline__ d4 widen16_half(const f4 &packed, int hh)
-{
-    typedef unsigned u4 __attribute__((ext_vector_type(4)));
-    const u4 w = __builtin_bit_cast(u4, packed);
-    d4 out;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const unsigned pair = hh == 0 ? w[e >> 1] : w[2 + (e >> 1)];
-        const unsigned h = (pair >> (16 * (e & 1))) & 0xffffu;
-        out[e] = static_cast<double>(IEEE_HALF ? f16_bits_to_float(h) : bf16_bits_to_float(h));
-    }
-    return out;
-}
-
-// eight doubles -> one packed 16-bit slice, each rounded once (nearest even)
-template <bool IEEE_HALF>
-__device__ __forceinline__ f4 narrow16_once(const d4 &lo, const d4 &hi)
-{
-    typedef unsigned u4 __attribute__((ext_vector_type(4)));
-    typedef float f2 __attribute__((ext_vector_type(2)));
-    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
-    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-    u4 w;
-#pragma unroll
-    for (int pair = 0; pair < 4; ++pair) {
-        const d4 &src = pair < 2 ? lo : hi;
-        const f2 two = {to_f32_round_to_odd(src[2 * (pair & 1)]), to_f32_round_to_odd(src[2 * (pair & 1) + 1])};
-        if constexpr (IEEE_HALF) w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, h2));
-        else w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
-    }
-    return __builtin_bit_cast(f4, w);
 }
 
 // cx_sgd_fused_mix_bf16 / _f16: FusedOp with 16-bit x and g rows and fp32 momentum rows.

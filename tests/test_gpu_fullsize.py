@@ -138,21 +138,10 @@ def test_c3_16bit_hierarchical_sampled_all_rounds(fmt):
         mix(a, b, wl.P, wl.G, sod, t)
         a, b = b, a
         mix(c, c, wl.P, wl.G, sod, t)
-        sub = O.hier_mix16_f32(fmt, sub, len(cols), wl.G, sso, tabs[r])
+        sub = O.hier_mix16(fmt, sub, len(cols), wl.G, sso, tabs[r])
     torch.cuda.synchronize()
     assert (grab(a) == sub).all() and (grab(c) == sub).all()
     free(a, b, c, xd)
-
-
-def hier_bound(xsub, G, ysub64, pe, sso):
-    W, n = xsub.shape
-    L = W // G
-    a = np.abs(xsub.astype(np.float64)).reshape(L, G, n).mean(1)
-    scale = a.copy()
-    for s in range(len(sso) - 1):
-        c0, c1 = sso[s], sso[s + 1]
-        scale[:, c0:c1] = 0.5 * (a[:, c0:c1] + a[pe[s], c0:c1])
-    return REL * np.maximum(np.abs(ysub64), np.repeat(scale, G, axis=0))
 
 
 @pytest.mark.parametrize("name", ["C3", "C5"])
@@ -168,6 +157,7 @@ def test_hierarchical_workloads_sampled_all_rounds(name):
     sub = take(xd, cold)
     a, b = xd, torch.empty_like(xd)
     sod = dev(so)
+    worst = 0.0
     for r in range(wl.rounds):
         t = dev(tabs[r])
         before = take(a, cold)
@@ -177,13 +167,17 @@ def test_hierarchical_workloads_sampled_all_rounds(name):
         else:
             cx.cx_hier_mix(a, a, wl.P, wl.G, sod, t)
         after = take(a, cold)
-        # every round: one step of the fp64 reference from the device's own input
+        # every round: one step of the fp64 reference from the device's own input; rounded once it is the
+        # device's output, so the benchmark's 1e-6 holds relative to the result itself
         y64 = O.hier_mix_f64(before, len(cols), wl.G, sso, tabs[r])
-        assert (np.abs(after - y64) <= hier_bound(before, wl.G, y64, tabs[r], sso)).all(), r
-        sub = O.hier_mix_f32(sub, len(cols), wl.G, sso, tabs[r])
-        assert same_bits(after, sub), r      # and the fixed-order fp32 trajectory, bit for bit
+        assert same_bits(after, once(y64)) and within_rel(after, y64), r
+        worst = max(worst, worst_rel(after, y64))
+        sub = once(O.hier_mix_f64(sub, len(cols), wl.G, sso, tabs[r]))
+        assert same_bits(after, sub), r      # and the oracle's own trajectory from the initial state
     grouped = after.reshape(wl.L, wl.G, -1)
     assert (grouped == grouped[:, :1]).all()
+    print(f"{name} hierarchical: worst relative error against the fp64 oracle over {wl.rounds} rounds: {worst:.3g}")
+    assert worst <= 2.0 ** -24
     free(a, b, xd)
 
 

@@ -239,3 +239,25 @@ def test_hier_fused16_special_cases(fmt):
     vn = np.float32(0.9).astype(np.float64) * v[0] + (gbar + np.float32(1e-4).astype(np.float64) * xl)
     assert np.abs(one[1][0] - vn).max() < 1e-12
     assert np.abs(one[0] - (xl - np.float32(0.1).astype(np.float64) * vn)).max() < 1e-12
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_array_narrowing_and_the_once_rounded_hierarchical_step(fmt):
+    f = FMT[fmt]
+    rng = np.random.default_rng(31)
+    d = np.ldexp(rng.standard_normal(5000), rng.integers(-30, 18, 5000))
+    assert (O.narrow16(fmt, d) == f["narrow"](d)).all()                       # the array form is the scalar one
+    W, G, P, S = 12, 4, 50, 3
+    x = rows16(fmt, WL.gen_matrix(W, P, 0.05, 32))
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(32, W // G, S, 0, 1)[0]
+    y64 = O.hier_mix16_f64(fmt, x, P, G, so, pe)                              # pinned in test_oracle_mix.py
+    got = O.hier_mix16(fmt, x, P, G, so, pe)
+    assert (got == f["narrow"](y64)).all()
+    assert (got.reshape(W // G, G, P) == got.reshape(W // G, G, P)[:, :1]).all()
+    # one rounding: a group whose exact mean sits 2^-31 above a tie goes up, where an fp32 sum would tie
+    ulp = 2.0 ** -f["keep"]
+    tie = rows16(fmt, [[1.0], [1.0 + ulp], [1.0], [1.0 + ulp]])              # mean 1 + ulp/2, exactly the tie
+    assert O.hier_mix16(fmt, tie, 1, 4, [0, 1], None).ravel().tolist() == [int(rows16(fmt, [1.0])[0])] * 4
+    up = rows16(fmt, [[1.0 + 2 * ulp], [1.0 + ulp], [1.0], [1.0 + ulp]])     # mean 1 + ulp: representable
+    assert O.hier_mix16(fmt, up, 1, 4, [0, 1], None).ravel().tolist() == [int(rows16(fmt, [1.0 + ulp])[0])] * 4
