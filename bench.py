@@ -189,6 +189,31 @@ class Runner:
                         "frac_of_hbm_peak": alg / (t * 1e-3) / 1e9 / HBM_PEAK_GBPS})
         return out
 
+    def buffer_pairs(self, count, steps):
+        """Out-of-place calls between every ordered pair of `count` allocations of the matrix (all alive at
+        once): kernel time per (source, destination), median over `steps` calls.  Shows which of the two
+        buffers' placement sets the rate."""
+        torch = self.torch
+        bufs = [self.x, self.y] + [torch.empty_like(self.x) for _ in range(count - 2)]
+        for b in bufs[1:]:
+            b.copy_(bufs[0])
+        alg = self.wl.W * self.wl.P * self.bytes_per_elem
+        out = []
+        for i in range(count):
+            for j in range(count):
+                if i == j:
+                    continue
+                self.ev = []
+                for k in range(steps + 1):
+                    self.x, self.y = bufs[i], bufs[j]
+                    self.step(k > 0)
+                torch.cuda.synchronize()
+                t = float(np.median([a.elapsed_time(b) for a, b in self.ev]))
+                out.append({"source": i, "destination": j, "kernel_ms_median": t,
+                            "frac_of_hbm_peak": alg / (t * 1e-3) / 1e9 / HBM_PEAK_GBPS})
+        self.x, self.y = bufs[0], bufs[1]
+        return {"addresses": [hex(b.data_ptr()) for b in bufs], "pairs": out}
+
     def whole_step_latency(self, rounds):
         """One step at a time, the device idle before and after: host clock around topology generation,
         table upload, launch and completion.  Median and minimum over `rounds` steps, in ms."""
@@ -401,6 +426,8 @@ def main():
                     help="launch parameters for cx_set_tuning (see include/cx_mix.h), e.g. 6=8,1=4")
     ap.add_argument("--allocations", type=int, default=0, metavar="K",
                     help="also time the calls on K allocations of the matrix within this process (placement spread)")
+    ap.add_argument("--buffer-pairs", type=int, default=0, metavar="K",
+                    help="also time out-of-place calls between every ordered pair of K allocations (gossip, hier)")
     ap.add_argument("--in-place", action="store_true",
                     help="update the matrix in place (cycle-walk kernel) instead of ping-pong buffers")
     args = ap.parse_args()
@@ -428,7 +455,10 @@ def main():
         sys.exit("bench.py: --bf16 / --f16 are not available for the push-sum comparison")
     latency_rounds = min(wl.rounds, 20)
     spread_steps = min(args.steps, 8)
-    runner = Runner(wl, kind, args.steps + args.warmup + latency_rounds + args.allocations * (spread_steps + 2),
+    if args.buffer_pairs and (args.in_place or kind not in ("gossip", "hier") or args.buffer_pairs < 2):
+        sys.exit("bench.py: --buffer-pairs K needs K >= 2 and an out-of-place gossip or hierarchical call")
+    pair_rounds = args.buffer_pairs * (args.buffer_pairs - 1) * (spread_steps + 1)
+    runner = Runner(wl, kind, args.steps + args.warmup + latency_rounds + args.allocations * (spread_steps + 2) + pair_rounds,
                     in_place=args.in_place, rows16=rows16)
     res = runner.run(args.steps, args.warmup)
     traffic, traffic_source = profiled_traffic(wl.name, kind, args.in_place, rows16, tuning)
@@ -460,6 +490,8 @@ def main():
     out["topology_gen"] = topology_gen_time(runner)
     if args.allocations:
         out["allocation_spread"] = runner.allocation_spread(args.allocations, spread_steps)
+    if args.buffer_pairs:
+        out["buffer_pairs"] = runner.buffer_pairs(args.buffer_pairs, spread_steps)
     if not args.no_copy:
         out["copy_ceiling"] = copy_ceiling(res["alg_bytes_per_launch"])
     del runner

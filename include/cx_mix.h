@@ -336,7 +336,7 @@ int cx_hier_sgd_fused_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float
  *   key 8: out of place: rows ordered along the permutation cycles (0 never, 1 always; default: from 64 MiB)
  *   key 9: resident workgroups per CU, both kernels (1..16; 0 = as many as fit)
  *   key 10: cx_hier_mix, G = 8, out of place: 1 = reduce the group through LDS, one row per wavefront
- *           (same results as the default register tree; kept for side-by-side measurement)
+ *           (same results as the default sum in registers; kept for side-by-side measurement)
  * A (key 0, key 3) pair that an operator was not built with falls back to its default.
  * cx_set_tuning returns CX_ERR_SHAPE for an unknown key or value; a value of -1 restores
  * the default.

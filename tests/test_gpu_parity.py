@@ -559,7 +559,7 @@ def test_hier_rounds_under_every_launch_shape(tuning):
 @pytest.mark.parametrize("cluster", [1, 2, 5, -1])
 def test_hier_mean_staged_through_lds_gives_the_same_bits(cluster):
     """Launch parameter 10: groups of 8 reduced through LDS (one row per wavefront).  Chunks wholly
-    inside a segment take that path, the others the register tree; every bit must equal the oracle's
+    inside a segment take that path, the others the sum in registers; every bit must equal the oracle's
     fixed-order result either way.  Ragged end, a short first segment, and an empty one."""
     W, G, P, ld, R = 64, 8, 150_001, 150_016, 3
     so = np.array([0, 1500, 1500, 70_000, 110_000, P], dtype=np.int64)
