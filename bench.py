@@ -56,7 +56,7 @@ def describe(wl, rows="fp32") -> str:
 class Runner:
     """Holds one workload's device state and issues its steps."""
 
-    def __init__(self, wl, kind, total_rounds, in_place=False, rows16=None):
+    def __init__(self, wl, kind, total_rounds, in_place=False, rows16=None, ld_multiple=1024, allocator="spread"):
         import torch
         from paper_2012_15198_amd import cxmix as cx
         from paper_2012_15198_amd import workloads as WL
@@ -68,35 +68,47 @@ class Runner:
         # layout: rows padded to a multiple of 1024 floats (4 KB) so every row starts on a cache
         # line and DRAM page boundary; two buffers, the rounds ping-pong between them
         self.in_place = in_place
-        self.ld = (wl.P + 1023) // 1024 * 1024
-        self.x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=self.ld, device=dev)
+        self.ld = (wl.P + ld_multiple - 1) // ld_multiple * ld_multiple
         self.rows16 = rows16                              # None (fp32 rows), "bf16" or "f16"
-        if rows16:
-            self.x = self.x.to(torch.bfloat16 if rows16 == "bf16" else torch.float16)
-        self.y = self.x if in_place else torch.empty_like(self.x)
+        rows_dt = {None: torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[rows16]
         self.n = wl.L if kind in ("hier", "hiersgd") else wl.W
         self.S = 1 if kind == "pushsum" else wl.S
         self.mode = 1 if kind == "pushsum" else 0
+        # every matrix of the job from one placement call: x and x' (one buffer when in place), and for the
+        # optimizer steps the fp32 momentum v, v' and the gradients g (rows of x's type)
+        full = (wl.W, self.ld)
+        want = [("x", full, rows_dt)] + ([] if in_place else [("y", full, rows_dt)])
+        if kind in ("fused", "hiersgd"):
+            vshape = full if kind == "fused" else (wl.L, self.ld)
+            want += [("v", vshape, torch.float32)] + ([] if in_place else [("v2", vshape, torch.float32)])
+            want += [("g", full, rows_dt)]
+        self.allocator = allocator
+        if allocator == "spread":
+            try:
+                bufs = cx.hbm_empty([w[1] for w in want], [w[2] for w in want], device=dev)
+            except (cx.CxError, RuntimeError) as e:       # placement is an optimisation: say so and go on
+                print(f"bench.py: cx_hbm_alloc unavailable ({e}); using torch's allocator", file=sys.stderr)
+                self.allocator = f"torch (cx_hbm_alloc failed: {e})"
+                bufs = None
+        if allocator != "spread" or bufs is None:
+            bufs = [torch.empty(w[1], dtype=w[2], device=dev) for w in want]
+        for (name, _, _), t in zip(want, bufs):
+            setattr(self, name, t)
+        if in_place:
+            self.y = self.x
+        WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=self.ld, device=dev, out=self.x)
         # one pinned + one device slot per round, so the host can run ahead of the GPU
         self.tab_host = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, pin_memory=True)
         self.tab_np = self.tab_host.numpy()
         self.tab_dev = torch.empty((total_rounds, self.S, self.n), dtype=torch.int32, device=dev)
         self.bytes_per_elem = bytes_per_element(kind, wl.G, rows16)
-        dt16 = (torch.bfloat16 if rows16 == "bf16" else torch.float16) if rows16 else None
-        if kind == "fused":
-            self.v = torch.zeros((wl.W, self.ld), device=dev)              # the momentum stays fp32
-            self.v2 = self.v if in_place else torch.empty_like(self.v)
-            self.g = WL.gen_matrix_device(wl.W, wl.P, wl.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
-            if rows16:
-                self.g = self.g.to(dt16)
-        if kind == "hiersgd":
-            c4 = WL.WORKLOADS["C4"]            # optimizer constants and gradient scale of C4
+        if kind in ("fused", "hiersgd"):
+            c4 = WL.WORKLOADS["C4"]            # the hierarchical step takes C4's optimizer constants and gradient scale
             self.lr, self.mu, self.wd = c4.lr, c4.mu, c4.wd
-            self.v = torch.zeros((wl.L, self.ld), device=dev)
-            self.v2 = self.v if in_place else torch.empty_like(self.v)
-            self.g = WL.gen_matrix_device(wl.W, wl.P, c4.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev)
-            if rows16:
-                self.g = self.g.to(dt16)
+            self.v.zero_()                                                 # the momentum stays fp32
+            if in_place:
+                self.v2 = self.v
+            WL.gen_matrix_device(wl.W, wl.P, c4.grad_sigma, wl.seed, ld=self.ld, stream=2, device=dev, out=self.g)
         if kind == "pushsum":
             self.w = [torch.ones(wl.W, device=dev), torch.zeros(wl.W, device=dev)]
         self.round = 0
@@ -194,9 +206,10 @@ class Runner:
         once): kernel time per (source, destination), median over `steps` calls.  Shows which of the two
         buffers' placement sets the rate."""
         torch = self.torch
-        bufs = [self.x, self.y] + [torch.empty_like(self.x) for _ in range(count - 2)]
-        for b in bufs[1:]:
-            b.copy_(bufs[0])
+        keep = (self.x, self.y)
+        bufs = [torch.empty_like(self.x) for _ in range(count)]       # plain allocations, one after the other
+        for b in bufs:
+            b.copy_(self.x)
         alg = self.wl.W * self.wl.P * self.bytes_per_elem
         out = []
         for i in range(count):
@@ -211,7 +224,7 @@ class Runner:
                 t = float(np.median([a.elapsed_time(b) for a, b in self.ev]))
                 out.append({"source": i, "destination": j, "kernel_ms_median": t,
                             "frac_of_hbm_peak": alg / (t * 1e-3) / 1e9 / HBM_PEAK_GBPS})
-        self.x, self.y = bufs[0], bufs[1]
+        self.x, self.y = keep
         return {"addresses": [hex(b.data_ptr()) for b in bufs], "pairs": out}
 
     def whole_step_latency(self, rounds):
@@ -270,13 +283,17 @@ def profiled_traffic(workload, kind, in_place, rows16=None, tuning=None):
     return traffic, f"profiles/{name} (kernel sources {src})"
 
 
-def copy_ceiling(nbytes, reps=10):
-    """Plain streaming copy with the same footprint split (read n/2, write n/2)."""
+def copy_ceiling(nbytes, reps=10, allocator="spread"):
+    """Plain streaming copy with the same footprint split (read n/2, write n/2), its two buffers placed
+    like the workload's."""
     import torch
     from paper_2012_15198_amd import cxmix as cx
     n = (nbytes // 8) // 4 * 4
-    src = torch.empty(n, dtype=torch.float32, device="cuda:0").normal_()
-    dst = torch.empty_like(src)
+    if allocator == "spread":
+        src, dst = cx.hbm_empty([(n,), (n,)])
+    else:
+        src, dst = torch.empty(n, dtype=torch.float32, device="cuda:0"), torch.empty(n, dtype=torch.float32, device="cuda:0")
+    src.normal_()
     for _ in range(2):
         cx.cx_copy_baseline(src, dst)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -428,6 +445,9 @@ def main():
                     help="also time the calls on K allocations of the matrix within this process (placement spread)")
     ap.add_argument("--buffer-pairs", type=int, default=0, metavar="K",
                     help="also time out-of-place calls between every ordered pair of K allocations (gossip, hier)")
+    ap.add_argument("--allocator", default=None, choices=["spread", "torch"],
+                    help="where the matrices come from: cx_hbm_alloc (every buffer spread over the physical memory; "
+                         "the default) or torch's allocator (hipMalloc; the default with --allocations / --buffer-pairs)")
     ap.add_argument("--in-place", action="store_true",
                     help="update the matrix in place (cycle-walk kernel) instead of ping-pong buffers")
     args = ap.parse_args()
@@ -458,8 +478,9 @@ def main():
     if args.buffer_pairs and (args.in_place or kind not in ("gossip", "hier") or args.buffer_pairs < 2):
         sys.exit("bench.py: --buffer-pairs K needs K >= 2 and an out-of-place gossip or hierarchical call")
     pair_rounds = args.buffer_pairs * (args.buffer_pairs - 1) * (spread_steps + 1)
+    allocator = args.allocator or ("torch" if args.allocations or args.buffer_pairs else "spread")
     runner = Runner(wl, kind, args.steps + args.warmup + latency_rounds + args.allocations * (spread_steps + 2) + pair_rounds,
-                    in_place=args.in_place, rows16=rows16)
+                    in_place=args.in_place, rows16=rows16, allocator=allocator)
     res = runner.run(args.steps, args.warmup)
     traffic, traffic_source = profiled_traffic(wl.name, kind, args.in_place, rows16, tuning)
     out = {
@@ -473,6 +494,8 @@ def main():
                    "entry_point": entry_point(kind, rows16),
                    "rounds_timed": args.steps, "in_place": bool(args.in_place), "ld": runner.ld,
                    "buffers": "in place" if args.in_place else "ping-pong (x_in -> x_out, swapped every round)",
+                   "allocator": {"spread": "cx_hbm_alloc (each matrix in 256 MiB pieces spread over the free physical memory)",
+                                 "torch": "torch (hipMalloc)"}.get(runner.allocator, runner.allocator),
                    "step": "cx_topology_gen(1 round) + table upload + one mixing launch",
                    "tuning": tuning or "defaults"},
         "params_mixed_per_s": res["params_mixed_per_s"],
@@ -493,7 +516,7 @@ def main():
     if args.buffer_pairs:
         out["buffer_pairs"] = runner.buffer_pairs(args.buffer_pairs, spread_steps)
     if not args.no_copy:
-        out["copy_ceiling"] = copy_ceiling(res["alg_bytes_per_launch"])
+        out["copy_ceiling"] = copy_ceiling(res["alg_bytes_per_launch"], allocator="spread" if runner.allocator == "spread" else "torch")
     del runner
     torch.cuda.empty_cache()
     out["cpu_baseline"] = None if args.no_cpu_baseline else cpu_baseline(wl, kind, rows16)
@@ -509,7 +532,7 @@ def main():
             if name == args.workload and k == kind and r16 == rows16:
                 continue
             w2 = WL.WORKLOADS[name]
-            r = Runner(w2, k, 2 * w2.rounds + 3, in_place=args.in_place, rows16=r16)
+            r = Runner(w2, k, 2 * w2.rounds + 3, in_place=args.in_place, rows16=r16, allocator=allocator)
             rr = r.run(w2.rounds, 3)
             rr["workload"] = describe(w2, r16 or "fp32")
             rr["entry_point"] = entry_point(k, r16)

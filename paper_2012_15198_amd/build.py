@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libcxmix.so")
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = [os.path.join(CSRC, f) for f in ("cx_host.cpp", "cx_api_gossip.hip", "cx_api_hier.hip",
+SOURCES = [os.path.join(CSRC, f) for f in ("cx_host.cpp", "cx_hbm.cpp", "cx_api_gossip.hip", "cx_api_hier.hip",
                                            "cx_api_pushsum.hip", "cx_api_fused.hip", "cx_api_hiersgd.hip",
                                            "cx_api_bf16.hip", "cx_api_f16.hip", "cx_api_hier16.hip",
                                            "cx_api_noalloc.hip", "cx_api_fused16.hip")]

@@ -92,11 +92,12 @@ const char *cx_status_string(int status)
     case CX_ERR_ALIAS: return "CX_ERR_ALIAS";
     case CX_ERR_HIP: return "CX_ERR_HIP";
     case CX_ERR_UNSUPPORTED: return "CX_ERR_UNSUPPORTED";
+    case CX_ERR_MEMORY: return "CX_ERR_MEMORY";
     default: return "CX_ERR_UNKNOWN";
     }
 }
 
-int cx_abi_version(void) { return 2; }
+int cx_abi_version(void) { return 3; }
 
 int cx_topology_gen(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t R,
                     int32_t mode, int32_t *peers_host)

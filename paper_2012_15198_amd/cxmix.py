@@ -21,7 +21,7 @@ CX_MAX_ROWS = 1024
 CX_OK = 0
 STATUS = {0: "CX_OK", -1: "CX_ERR_NULL", -2: "CX_ERR_SHAPE", -3: "CX_ERR_SEGMENTS",
           -4: "CX_ERR_PEERS", -5: "CX_ERR_ALIGN", -6: "CX_ERR_ALIAS", -7: "CX_ERR_HIP",
-          -8: "CX_ERR_UNSUPPORTED"}
+          -8: "CX_ERR_UNSUPPORTED", -9: "CX_ERR_MEMORY"}
 CX_TOPO_FAIR, CX_TOPO_DIRECTED_EXP, CX_TOPO_UNFAIR, CX_TOPO_SAME_ALL_SEGMENTS = 0, 1, 2, 16
 TUNE_SLICES, TUNE_WAVES, TUNE_NONTEMPORAL, TUNE_DEPTH = 0, 1, 2, 3
 TUNE_LOCKSTEP, TUNE_FORCE_WALK, TUNE_CLUSTER, TUNE_XCD_AWARE, TUNE_ORDERED, TUNE_WGS_PER_CU = 4, 5, 6, 7, 8, 9
@@ -31,7 +31,7 @@ EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_se
            "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",
            "cx_sgd_fused_mix", "cx_hier_sgd_fused_mix", "cx_gossip_mix_noalloc", "cx_gossip_mix_bf16", "cx_gossip_mix_f16", "cx_hier_mix_bf16", "cx_hier_mix_f16",
            "cx_sgd_fused_mix_bf16", "cx_sgd_fused_mix_f16", "cx_hier_sgd_fused_mix_bf16", "cx_hier_sgd_fused_mix_f16",
-           "cx_copy_baseline", "cx_set_tuning",
+           "cx_hbm_alloc", "cx_hbm_free", "cx_copy_baseline", "cx_set_tuning",
            "cx_get_tuning"]
 
 
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, vp, vp, u32, vp]
     for name in ("cx_hier_sgd_fused_mix_bf16", "cx_hier_sgd_fused_mix_f16"):
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32, vp, vp, u32, vp]
+    L.cx_hbm_alloc.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(i64), i32, u32]
+    L.cx_hbm_free.argtypes = [vp]
     L.cx_copy_baseline.argtypes = [vp, vp, i64, vp]
     L.cx_set_tuning.argtypes = [i32, i32]
     L.cx_get_tuning.argtypes = [i32]
@@ -376,6 +378,57 @@ def cx_hier_sgd_fused_mix_f16(x_in, x_out, v_in, v_out, g, lr: float, mu: float,
     """x, g: float16 [W][ld]; v: float32 [W/G][ld], same ld."""
     _hier_fused16("cx_hier_sgd_fused_mix_f16", x_in, x_out, v_in, v_out, g, lr, mu, wd, P, G, seg_off_dev,
                   leader_peers_dev, flags, stream)
+
+
+def cx_hbm_alloc(sizes, flags: int = 0):
+    """Device addresses (ints) of len(sizes) blocks placed together; release each with cx_hbm_free."""
+    n = len(sizes)
+    ptrs = (ctypes.c_void_p * max(n, 1))()
+    nbytes = (ctypes.c_int64 * max(n, 1))(*[int(b) for b in sizes])
+    _ok("cx_hbm_alloc", lib().cx_hbm_alloc(ptrs, nbytes, n, flags))
+    return [int(p) for p in ptrs[:n]]
+
+
+def cx_hbm_free(ptr: int) -> None:
+    _ok("cx_hbm_free", lib().cx_hbm_free(ctypes.c_void_p(ptr)))
+
+
+class _HbmBlock:
+    """Owner of one block of cx_hbm_alloc: torch views it through the array interface and keeps this
+    object alive as long as a tensor (or a view of one) uses the memory; then the block is released."""
+
+    def __init__(self, ptr, shape, typestr):
+        self.ptr = ptr
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": typestr, "data": (ptr, False),
+                                         "version": 2, "strides": None}
+
+    def __del__(self):
+        try:
+            lib().cx_hbm_free(ctypes.c_void_p(self.ptr))
+        except Exception:            # interpreter shutdown: the process gives the memory back
+            pass
+
+
+def hbm_empty(shapes, dtypes=None, device="cuda:0"):
+    """Uninitialised torch tensors of the given shapes in memory from ONE cx_hbm_alloc call, so that every
+    tensor is spread over the device's physical memory.  `dtypes`: one torch dtype for all (default
+    float32) or one per shape; each block is handed to torch as integers of the element size and
+    reinterpreted, which covers float32, float16, bfloat16 and the integer types."""
+    import torch
+    shapes = [tuple(int(d) for d in sh) for sh in shapes]
+    if dtypes is None or isinstance(dtypes, torch.dtype):
+        dtypes = [dtypes or torch.float32] * len(shapes)
+    sizes = [torch.empty((), dtype=dt).element_size() for dt in dtypes]
+    carrier = {4: (torch.int32, "<i4"), 2: (torch.int16, "<i2"), 1: (torch.uint8, "|u1"), 8: (torch.int64, "<i8")}
+    with torch.cuda.device(device):
+        ptrs = cx_hbm_alloc([int(np.prod(sh, dtype=np.int64)) * sz for sh, sz in zip(shapes, sizes)])
+    out = []
+    for ptr, sh, dt, sz in zip(ptrs, shapes, dtypes, sizes):
+        t = torch.as_tensor(_HbmBlock(ptr, sh, carrier[sz][1]), device=device)
+        if t.data_ptr() != ptr or t.dtype != carrier[sz][0]:
+            raise RuntimeError("torch copied the block instead of viewing it")
+        out.append(t.view(dt))
+    return out
 
 
 def cx_copy_baseline(src, dst, stream=None):

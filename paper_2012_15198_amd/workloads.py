@@ -125,17 +125,25 @@ def gen_matrix(W: int, P: int, sigma: float, seed: int, ld: Optional[int] = None
 
 
 def gen_matrix_device(W: int, P: int, sigma: float, seed: int, ld: Optional[int] = None,
-                      stream: int = 0, device: str = "cuda:0"):
+                      stream: int = 0, device: str = "cuda:0", out=None):
     """Same shape/distribution as gen_matrix, drawn on the device by torch's
     generator (for the full-size workloads, where host generation is too slow).
-    The values differ from gen_matrix's; parity at full size downloads what it needs."""
+    The values differ from gen_matrix's; parity at full size downloads what it needs.
+    `out`: a [W][ld] device tensor to fill instead of a new one; float32 rows are drawn
+    in place, 16-bit rows are drawn in float32 and rounded to nearest even row by row."""
     import torch
     ld = P if ld is None else ld
     g = torch.Generator(device=device)
     g.manual_seed(seed * 1000003 + stream)
-    out = torch.empty((W, ld), dtype=torch.float32, device=device)
+    if out is None:
+        out = torch.empty((W, ld), dtype=torch.float32, device=device)
+    assert tuple(out.shape) == (W, ld)
+    row = None if out.dtype == torch.float32 else torch.empty(P, dtype=torch.float32, device=device)
     for i in range(W):
-        out[i, :P].normal_(0.0, sigma, generator=g)
+        if row is None:
+            out[i, :P].normal_(0.0, sigma, generator=g)
+        else:
+            out[i, :P].copy_(row.normal_(0.0, sigma, generator=g))
     if ld > P:
         out[:, P:] = 12345.0
     return out

@@ -22,7 +22,7 @@ def test_library_exports_every_symbol_the_header_declares():
     L = cx.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert cx.cx_abi_version() == 2
+    assert cx.cx_abi_version() == 3
     assert cx.cx_status_string(0) == "CX_OK" and cx.cx_status_string(-6) == "CX_ERR_ALIAS"
     for code, name in cx.STATUS.items():
         assert cx.cx_status_string(code) == name
@@ -217,6 +217,23 @@ def test_mix_calls_reject_bad_arguments_on_the_host():
     assert L.cx_copy_baseline(A, A + 64, 64, None) == -6
 
 
+def test_hbm_alloc_rejects_bad_requests_before_touching_the_device():
+    """cx_hbm_alloc / cx_hbm_free: every argument error is found before the first runtime call."""
+    L = cx.lib()
+    ptrs = (ctypes.c_void_p * 2)()
+    sizes = (ctypes.c_int64 * 2)(1 << 20, 1 << 20)
+    assert L.cx_hbm_alloc(None, sizes, 2, 0) == -1 and L.cx_hbm_alloc(ptrs, None, 2, 0) == -1
+    assert L.cx_hbm_alloc(ptrs, sizes, 0, 0) == -2 and L.cx_hbm_alloc(ptrs, sizes, 65, 0) == -2
+    assert L.cx_hbm_alloc(ptrs, (ctypes.c_int64 * 2)(1 << 20, 0), 2, 0) == -2
+    assert L.cx_hbm_alloc(ptrs, (ctypes.c_int64 * 2)(-5, 1), 2, 0) == -2
+    assert L.cx_hbm_alloc(ptrs, (ctypes.c_int64 * 2)((1 << 40) + 1, 1), 2, 0) == -2
+    assert L.cx_hbm_alloc(ptrs, sizes, 2, 1) == -8
+    assert L.cx_hbm_free(None) == -1
+    assert L.cx_hbm_free(ctypes.c_void_p(0x1000)) == -8          # not a live block of cx_hbm_alloc
+    with pytest.raises(cx.CxError, match="CX_ERR_SHAPE"):
+        cx.cx_hbm_alloc([])
+
+
 def test_tuning_keys():
     for key, good, bad in [(cx.TUNE_SLICES, 2, 3), (cx.TUNE_WAVES, 8, 9), (cx.TUNE_NONTEMPORAL, 0, 2),
                            (cx.TUNE_DEPTH, 8, 3), (cx.TUNE_LOCKSTEP, 1, 2), (cx.TUNE_FORCE_WALK, 1, 2),
@@ -250,7 +267,7 @@ int main(void)
     int32_t peers[R * S * N];
     int64_t seg_off[S + 1] = {0, 10, 20, 30};
     int r, s, i, rc;
-    if (cx_abi_version() != 2) return 10;
+    if (cx_abi_version() != 3) return 10;
     rc = cx_topology_gen(2u, N, S, 0, R, CX_TOPO_FAIR, peers);
     if (rc != CX_OK) return 11;
     for (r = 0; r < R; ++r)
