@@ -24,7 +24,7 @@ int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t 
     case 4: return launch_mix<MeanOp<4>>(MeanOp<4>{x_in, x_out, ld}, a);
     case 8:
         // launch parameter 10: the group mean staged through LDS (one row per wavefront) instead of the
-        // register tree -- same results, kept so that the two can be measured side by side
+        // sum in registers -- same results, kept so that the two can be measured side by side
         if (cx_get_tuning(10) == 1) return launch_mix<MeanLdsOp<8>>(MeanLdsOp<8>{{x_in, x_out, ld}}, a);
         return launch_mix<MeanOp<8>>(MeanOp<8>{x_in, x_out, ld}, a);
     case 16: return launch_mix<MeanOp<16>>(MeanOp<16>{x_in, x_out, ld}, a);

@@ -185,9 +185,10 @@ struct MeanOp {
     template <int U> using Work = std::conditional_t<G == 1, Tile<U>, WideTile<U>>;
     static constexpr int kRawPerSlice = G;
     // out-of-place launch: slices per lane, waves per workgroup, KB of one visit to a gossiping row
-    // (all G rows behind it) per XCD -- measured optima on MI355X
+    // (all G rows behind it) per XCD -- measured optima on MI355X, on matrices spread over the
+    // physical memory (cx_hbm_alloc)
     static constexpr GatherShape kGather =
-        G == 1 ? GatherShape{1, 4, 256, 0} : G <= 4 ? GatherShape{1, 8, 512, 0} : GatherShape{1, 8, 1024, 0};
+        G == 1 ? GatherShape{1, 4, 256, 0} : G <= 4 ? GatherShape{1, 8, 512, 0} : GatherShape{1, 8, 768, 0};
     static constexpr WalkShape kWalk =
         G == 1 ? WalkShape{1, 2, 2, 8} : G == 2 ? WalkShape{2, 4, 2, 2} : G <= 8 ? WalkShape{1, 4, 2, 2} : WalkShape{1, 2, 2, 2};
     template <int U> struct Raw { Tile<U> r[G]; };
@@ -233,7 +234,7 @@ struct MeanOp {
     }
 };
 
-// The hierarchical mean staged through LDS, kept for measurement next to the register tree (launch
+// The hierarchical mean staged through LDS, kept for measurement next to the sum in registers (launch
 // parameter 10).  A workgroup is G wavefronts and owns G tiles of 256 columns; wavefront j fetches
 // row j of its group and of the partner group (G contiguous 1-KB loads each), the rows meet in
 // LDS (G x G KB), wavefront w reduces tile w over the G rows in the same order and precision, and
@@ -337,7 +338,7 @@ struct FusedOp {
     static constexpr int kElems = 4;                       // fp32 columns per 16-byte slice
     template <int U> using Work = WideTile<U>;             // the updated row, in fp64
     static constexpr int kRawPerSlice = 3;
-    static constexpr GatherShape kGather{1, 8, 256, 3};
+    static constexpr GatherShape kGather{1, 8, 128, 3};
     static constexpr WalkShape kWalk{2, 2, 4, 2};
     static constexpr int kMaxU = 2;                        // fp64 rows: two slices per lane fill the registers
     template <int U> struct Raw { Tile<U> x, v, g; };
@@ -391,7 +392,7 @@ struct HierFusedOp {
     static constexpr int kRawPerSlice = G + 2;
     // out-of-place launch: slices, waves, group visit KB per XCD
     static constexpr GatherShape kGather =
-        G == 1 ? GatherShape{1, 8, 256, 0} : G <= 4 ? GatherShape{1, 8, 512, 0} : GatherShape{1, 8, 1024, 0};
+        G == 1 ? GatherShape{1, 8, 256, 0} : G <= 4 ? GatherShape{1, 8, 512, 0} : GatherShape{1, 8, 768, 0};
     static constexpr WalkShape kWalk = G <= 4 ? WalkShape{1, 4, 2, 2} : WalkShape{1, 2, 2, 2};
     static constexpr int kMaxU = G <= 2 ? 2 : 1;
     template <int U> struct Raw { Tile<U> g[G], x, v; };
@@ -547,7 +548,7 @@ struct Row16Op {
     template <int U> using Work = std::conditional_t<G == 1, Tile<2 * U>, WideTile<2 * U>>;   // 8 values per slice
     static constexpr int kRawPerSlice = G;
     static constexpr GatherShape kGather =
-        G == 1 ? GatherShape{1, 8, 128, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
+        G == 1 ? GatherShape{1, 8, 96, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 384, 0};
     static constexpr WalkShape kWalk = G == 1 ? WalkShape{1, 2, 8, 0} : WalkShape{1, 2, 2, 2};
     static constexpr int kMaxU = G == 1 ? 4 : 1;           // grouped: one slice per lane fills the registers
     template <int U> struct Raw { Tile<U> r[G]; };         // packed 16-bit pairs, as loaded
@@ -729,7 +730,7 @@ struct Fused16Op {
     static constexpr int kElems = 8;                       // 16-bit columns per 16-byte slice
     template <int U> using Work = WideTile<2 * U>;         // the updated row, 8 doubles per slice
     static constexpr int kRawPerSlice = 4;                 // x, g: one register each; v: two
-    static constexpr GatherShape kGather{1, 4, 192, 0};
+    static constexpr GatherShape kGather{1, 4, 96, 0};
     static constexpr WalkShape kWalk{1, 2, 4, 2};
     static constexpr int kMaxU = 1;
     static constexpr int kStageBytes = kStageBytesPerWave; // LDS per wavefront (see tile_load8)
@@ -786,7 +787,7 @@ struct HierFused16Op {
     template <int U> using Work = WideTile<2 * U>;
     static constexpr int kRawPerSlice = G + 3;             // G gradient rows, x, and two registers of v
     static constexpr GatherShape kGather =
-        G == 1 ? GatherShape{1, 8, 192, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 512, 0};
+        G == 1 ? GatherShape{1, 8, 192, 0} : G <= 4 ? GatherShape{1, 8, 256, 0} : GatherShape{1, 8, 384, 0};
     static constexpr WalkShape kWalk{1, 2, 2, 2};
     static constexpr int kMaxU = 1;
     static constexpr int kStageBytes = kStageBytesPerWave;
