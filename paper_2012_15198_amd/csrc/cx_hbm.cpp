@@ -113,7 +113,17 @@ int cx_hbm_alloc(void **ptrs_out, const int64_t *bytes, int32_t count, uint32_t 
             fillers.push_back(h);
             done += piece;
         }
-        if (hipMemCreate(&p.handle, p.bytes, &prop, 0) != hipSuccess) {
+        hipError_t made = hipMemCreate(&p.handle, p.bytes, &prop, 0);
+        if (made != hipSuccess && !fillers.empty()) {
+            // the fillers took what the piece needs (less was free than reported, or somebody else
+            // allocated meanwhile): give them back, place the rest without skipping
+            (void)hipGetLastError();
+            for (hipMemGenericAllocationHandle_t h : fillers) (void)hipMemRelease(h);
+            fillers.clear();
+            fill = false;
+            made = hipMemCreate(&p.handle, p.bytes, &prop, 0);
+        }
+        if (made != hipSuccess) {
             (void)hipGetLastError();
             status = CX_ERR_MEMORY;
             break;

@@ -7,7 +7,10 @@ code the kernels share with the host, and the oracle.  CPU only; every build goe
   * tests/host/host_half_check.cpp: csrc/cx_host.cpp and oracle/cx_oracle.c in one ASan + UBSan program:
     topologies of both compared for every mode, the table checkers, every oracle function on exact-size
     heap buffers;
-  * the oracle's own pin tests re-run against an ASan + UBSan build of the oracle."""
+  * the oracle's own pin tests re-run against an ASan + UBSan build of the oracle;
+  * tests/host/hbm_policy_check.cpp: csrc/cx_hbm.cpp (placement of the matrices in physical memory) against a model
+    of device memory behind a stand-in runtime header: where the pieces land, what is given back, and every
+    runtime call failing once at every position -- paths that must not be provoked on a GPU."""
 import os
 import subprocess
 import sys
@@ -50,6 +53,13 @@ def test_host_half_and_oracle_under_address_and_ub_sanitizers(tmp_path):
     exe = tmp_path / "host_half"
     run(["g++", "-std=c++17", *SAN, "-Wall", "-Wextra", "-I", os.path.join(ROOT, "include"),
          os.path.join(HOST, "host_half_check.cpp"), os.path.join(CSRC, "cx_host.cpp"), str(obj), "-o", str(exe), "-lm"])
+    assert run([str(exe)], env=ENV).strip().endswith("ok")
+
+
+def test_placement_policy_and_its_error_paths_against_a_model_of_device_memory(tmp_path):
+    exe = tmp_path / "hbm_policy"
+    run(["g++", "-std=c++17", *SAN, "-Wall", "-Wextra", "-I", os.path.join(HOST, "fake_hip"), "-I", os.path.join(ROOT, "include"),
+         os.path.join(HOST, "hbm_policy_check.cpp"), os.path.join(CSRC, "cx_hbm.cpp"), "-o", str(exe)])
     assert run([str(exe)], env=ENV).strip().endswith("ok")
 
 
