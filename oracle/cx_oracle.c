@@ -30,7 +30,10 @@
  * rational nearest-value search (every tie, the overflow point, the subnormal range) and
  * numpy; the optimizer steps on 16-bit rows by hand (one case that tells one rounding from
  * rounding through fp32), against the fp32-row steps on widened rows and against
- * torch.optim.SGD.  No function here is "parity unpinned".
+ * torch.optim.SGD; the push-sum round on 16-bit rows by hand on exact values, its
+ * invariants (column sums, weight sum, z * w' = x'), the exponential graph reaching the
+ * mean in log2 W rounds, its rounding against the double reference, and against the
+ * fp32-row round between the pinned conversions.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -758,6 +761,47 @@ int oracle_pushsum_mix_f32(const float *x_in, const float *w_in, float *x_out,
         w_out[i] = wn;
         for (int64_t c = 0; c < P; ++c) {
             float xn = (x_in[i * ld + c] + x_in[j * ld + c]) * 0.5f;
+            x_out[i * ld + c] = xn;
+            if (z_out) z_out[i * ld + c] = xn / wn;
+        }
+    }
+    return 0;
+}
+
+/* Push-sum on 16-bit rows (Section 4.1's mixed precision applied to the SGP comparison of Sections 2.1 and 3):
+ * the parameter rows are bfloat16 (fmt 0) or binary16 (fmt 1), the push-sum weights stay fp32.  The rows are
+ * widened exactly and the round is the fp32 one above, value for value:
+ *     xn = (float(x_i) + float(x_{i-hop})) * 0.5f ;  wn = (w_i + w_{i-hop}) * 0.5f ;
+ *     x'_i = round16(xn) ;  z_i = round16(xn / wn)        (z from the unrounded fp32 average)
+ * with round16 = round to nearest even into the row format.  The _f64 variant returns the same quantities
+ * in double arithmetic, unrounded, as the reference the 16-bit results are measured against. */
+int oracle_pushsum_mix16(int fmt, const uint16_t *x_in, const float *w_in, uint16_t *x_out, float *w_out,
+                         uint16_t *z_out /* may be NULL */, int64_t ld, int32_t W, int64_t P, int32_t hop)
+{
+    if (fmt != 0 && fmt != 1) return -1;
+    for (int32_t i = 0; i < W; ++i) {
+        int32_t j = ((i - hop) % W + W) % W;
+        float wn = (w_in[i] + w_in[j]) * 0.5f;
+        w_out[i] = wn;
+        for (int64_t c = 0; c < P; ++c) {
+            float xn = (widen16(fmt, x_in[i * ld + c]) + widen16(fmt, x_in[j * ld + c])) * 0.5f;
+            x_out[i * ld + c] = narrow16(fmt, xn);
+            if (z_out) z_out[i * ld + c] = narrow16(fmt, xn / wn);
+        }
+    }
+    return 0;
+}
+
+int oracle_pushsum_mix16_f64(int fmt, const uint16_t *x_in, const float *w_in, double *x_out, double *w_out,
+                             double *z_out /* may be NULL */, int64_t ld, int32_t W, int64_t P, int32_t hop)
+{
+    if (fmt != 0 && fmt != 1) return -1;
+    for (int32_t i = 0; i < W; ++i) {
+        int32_t j = ((i - hop) % W + W) % W;
+        double wn = ((double)w_in[i] + (double)w_in[j]) * 0.5;
+        w_out[i] = wn;
+        for (int64_t c = 0; c < P; ++c) {
+            double xn = ((double)widen16(fmt, x_in[i * ld + c]) + (double)widen16(fmt, x_in[j * ld + c])) * 0.5;
             x_out[i * ld + c] = xn;
             if (z_out) z_out[i * ld + c] = xn / wn;
         }

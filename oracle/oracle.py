@@ -25,7 +25,8 @@ __all__ = ["build_oracle", "mix64", "key", "draw", "uniform", "fair_draw", "topo
            "hier_sgd_fused_mix_f64", "hier_sgd_fused_mix_f32", "gossip_mix_bf16", "f32_to_bf16",
            "bf16_to_f32", "gossip_mix_f16", "f32_to_f16", "f16_to_f32", "hier_mix16_f64", "hier_mix16_f32",
            "f64_to_bf16", "f64_to_f16", "sgd_fused_mix16_f64", "sgd_fused_mix16",
-           "hier_sgd_fused_mix16_f64", "hier_sgd_fused_mix16", "narrow16", "hier_mix16"]
+           "hier_sgd_fused_mix16_f64", "hier_sgd_fused_mix16", "narrow16", "hier_mix16",
+           "pushsum_mix16", "pushsum_mix16_f64"]
 
 
 def build_oracle(force: bool = False) -> str:
@@ -89,6 +90,8 @@ def _L():
         lib.oracle_hier_mix16.argtypes = [i32, vp, vp, i64, i32, i64, i32, i32, vp, vp]
         lib.oracle_pushsum_mix_f64.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
         lib.oracle_pushsum_mix_f32.argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32]
+        lib.oracle_pushsum_mix16.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i64, i32]
+        lib.oracle_pushsum_mix16_f64.argtypes = [i32, vp, vp, vp, vp, vp, i64, i32, i64, i32]
         _lib = lib
     return _lib
 
@@ -406,3 +409,28 @@ def hier_mix16(fmt, x, P, G, seg_off, leader_peers) -> np.ndarray:
     """The hierarchical step on 16-bit rows in double with ONE rounding to the 16-bit format: uint16 [W][ld]."""
     x = _mat(x, dtype=np.uint16)
     return _hier16(_L().oracle_hier_mix16, fmt, x, x.copy(), P, G, seg_off, leader_peers)
+
+
+def _push16(fn, odtype, fmt, x, w, P, hop, want_z):
+    x = _mat(x, dtype=np.uint16)
+    W, ld = x.shape
+    w = np.ascontiguousarray(w, dtype=np.float32).reshape(W)
+    if not 1 <= hop < W:
+        raise ValueError("hop must be in [1, W)")
+    xo = x.copy() if odtype == np.uint16 else np.zeros(x.shape, dtype=np.float64)
+    wo = w.astype(np.float32 if odtype == np.uint16 else np.float64)
+    zo = xo.copy() if want_z else None
+    _check(fn(_FMT[fmt], _p(x), _p(w), _p(xo), _p(wo), _p(zo), ld, W, P, hop), "pushsum_mix16")
+    return xo, wo, zo
+
+
+def pushsum_mix16(fmt, x, w, P, hop, want_z=True):
+    """Push-sum round on 16-bit rows ("bf16" / "f16" bit patterns, uint16 [W][ld]), fp32 weights:
+    (x' patterns, w' float32, z patterns or None).  Padding columns of x' and z keep x's."""
+    return _push16(_L().oracle_pushsum_mix16, np.uint16, fmt, x, w, P, hop, want_z)
+
+
+def pushsum_mix16_f64(fmt, x, w, P, hop, want_z=True):
+    """The same round in double arithmetic, unrounded (float64 arrays; padding columns zero)."""
+    return _push16(_L().oracle_pushsum_mix16_f64, np.float64, fmt, x, w, P, hop, want_z)
+
