@@ -144,7 +144,8 @@ class Runner:
             self.v, self.v2 = self.v2, self.v
         elif self.kind == "pushsum":
             hop = int((0 - int(self.tab_np[r, 0, 0])) % wl.W)
-            cx.cx_pushsum_mix(self.x, self.y, self.w[r & 1], self.w[1 - (r & 1)], None, wl.P, hop)
+            push = {None: cx.cx_pushsum_mix, "bf16": cx.cx_pushsum_mix_bf16, "f16": cx.cx_pushsum_mix_f16}[self.rows16]
+            push(self.x, self.y, self.w[r & 1], self.w[1 - (r & 1)], None, wl.P, hop)
         self.x, self.y = self.y, self.x
         if timed:
             e1.record()
@@ -349,7 +350,7 @@ def cpu_baseline(wl, kind, rows16=None, budget_s=12.0, max_bytes=8 << 30):
             "fused": "oracle_sgd_fused_mix_f64", "hiersgd": "oracle_hier_sgd_fused_mix_f64"}[kind]
     if fmt:
         name = {"gossip": f"oracle_gossip_mix_{fmt}", "hier": "oracle_hier_mix16", "fused": "oracle_sgd_fused_mix16",
-                "hiersgd": "oracle_hier_sgd_fused_mix16"}[kind]
+                "hiersgd": "oracle_hier_sgd_fused_mix16", "pushsum": "oracle_pushsum_mix16"}[kind]
     x = v = g = so = spare = None
     w = np.ones(wl.W, dtype=np.float32)
     P = 0
@@ -377,7 +378,8 @@ def cpu_baseline(wl, kind, rows16=None, budget_s=12.0, max_bytes=8 << 30):
         elif kind == "hier":
             x = O.hier_mix_f64(x, P, wl.G, so, t).astype(np.float32) if not fmt else O.hier_mix16(fmt, x, P, wl.G, so, t)
         elif kind == "pushsum":
-            x, w, _ = O.pushsum_mix_f32(x, w, P, int((0 - int(t[0, 0])) % wl.W), False)
+            hop = int((0 - int(t[0, 0])) % wl.W)
+            x, w, _ = O.pushsum_mix16(fmt, x, w, P, hop, False) if fmt else O.pushsum_mix_f32(x, w, P, hop, False)
         elif kind == "fused":
             if fmt:
                 x, v = O.sgd_fused_mix16(fmt, x, v, g, lr, mu, wd, P, so, t)
@@ -437,8 +439,8 @@ def main():
     ap.add_argument("--all", action="store_true", help="also time the other workloads' entry points")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy", action="store_true")
-    ap.add_argument("--bf16", action="store_true", help="bfloat16 rows: cx_gossip_mix_bf16 / cx_hier_mix_bf16")
-    ap.add_argument("--f16", action="store_true", help="binary16 rows: cx_gossip_mix_f16 / cx_hier_mix_f16")
+    ap.add_argument("--bf16", action="store_true", help="bfloat16 rows (every entry point has a _bf16 variant)")
+    ap.add_argument("--f16", action="store_true", help="binary16 rows (every entry point has a _f16 variant)")
     ap.add_argument("--tune", default="", metavar="KEY=VALUE[,KEY=VALUE...]",
                     help="launch parameters for cx_set_tuning (see include/cx_mix.h), e.g. 6=8,1=4")
     ap.add_argument("--allocations", type=int, default=0, metavar="K",
@@ -471,8 +473,6 @@ def main():
     if args.bf16 and args.f16:
         sys.exit("bench.py: --bf16 and --f16 exclude each other")
     rows16 = "bf16" if args.bf16 else "f16" if args.f16 else None
-    if rows16 and kind == "pushsum":
-        sys.exit("bench.py: --bf16 / --f16 are not available for the push-sum comparison")
     latency_rounds = min(wl.rounds, 20)
     spread_steps = min(args.steps, 8)
     if args.buffer_pairs and (args.in_place or kind not in ("gossip", "hier") or args.buffer_pairs < 2):
@@ -527,7 +527,8 @@ def main():
         others = {}
         plan = [("C1", "gossip", None), ("C2", "gossip", None), ("C2", "gossip", "bf16"), ("C2", "gossip", "f16"),
                 ("C3", "hier", None), ("C3", "hier", "bf16"), ("C3", "hiersgd", None), ("C3", "hiersgd", "bf16"),
-                ("C4", "fused", None), ("C4", "fused", "bf16"), ("C4", "pushsum", None), ("C5", "hier", None)]
+                ("C4", "fused", None), ("C4", "fused", "bf16"), ("C4", "pushsum", None), ("C4", "pushsum", "bf16"),
+                ("C5", "hier", None)]
         for name, k, r16 in plan:
             if name == args.workload and k == kind and r16 == rows16:
                 continue

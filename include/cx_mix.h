@@ -97,7 +97,7 @@ enum cx_topology_mode {
 /* Human-readable name of a status code (static storage). */
 const char *cx_status_string(int status);
 
-/* ABI version of this header (bumped on any signature change): 3. */
+/* ABI version of this header (bumped on any signature change): 4. */
 int cx_abi_version(void);
 
 /* ------------------------------------------------------------------------------------
@@ -322,6 +322,23 @@ int cx_hier_sgd_fused_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float
                               const uint16_t *g, float lr, float mu, float wd, int64_t ld, int32_t W,
                               int64_t P, int32_t G, int32_t S, const int64_t *seg_off_dev,
                               const int32_t *leader_peers_dev, uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * cx_pushsum_mix_bf16 / cx_pushsum_mix_f16 -- the push-sum comparison (Sections 2.1 and 3) on
+ * 16-bit parameter rows (Section 4.1's mixed precision): x_in, x_out and z_out are bit patterns,
+ * uint16 [W][ld] with ld % 8 == 0; the weights stay float32.  Rows are widened exactly and the
+ * round is cx_pushsum_mix's, value for value, each output narrowed once (nearest even):
+ *     j = (i - hop) mod W ;  a = (float(x_in[i]) + float(x_in[j])) * 0.5f
+ *     x_out[i] = round16(a) ;  w_out[i] = (w_in[i] + w_in[j]) * 0.5f
+ *     z_out[i] = round16(a / w_out[i])       (only if z_out != NULL; from the unrounded a)
+ * Errors and overlap rules as cx_pushsum_mix; CX_ERR_ALIGN if ld % 8 != 0.
+ */
+int cx_pushsum_mix_bf16(const uint16_t *x_in, uint16_t *x_out, const float *w_in, float *w_out,
+                        uint16_t *z_out, int64_t ld, int32_t W, int64_t P, int32_t hop,
+                        uint32_t flags, void *stream);
+int cx_pushsum_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float *w_in, float *w_out,
+                       uint16_t *z_out, int64_t ld, int32_t W, int64_t P, int32_t hop,
+                       uint32_t flags, void *stream);
 
 /* ------------------------------------------------------------------------------------
  * cx_hbm_alloc / cx_hbm_free -- device memory for the worker matrices, placed for the kernels

@@ -1,20 +1,6 @@
 // C-ABI entry point(s) cx_pushsum_mix: argument checks and launch (see include/cx_mix.h).
 #include "cx_kernels.hpp"
 
-namespace {
-
-// w_out[i] = (w_in[i] + w_in[(i - hop) mod n]) * 0.5f  (push-sum weights, n <= CX_MAX_ROWS)
-__global__ void pushsum_weight_kernel(const float *__restrict__ w_in, float *__restrict__ w_out,
-                                      int n, int hop)
-{
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-        const int from = i >= hop ? i - hop : i - hop + n;
-        w_out[i] = (w_in[i] + w_in[from]) * 0.5f;
-    }
-}
-
-}  // namespace
-
 extern "C" {
 
 int cx_pushsum_mix(const float *x_in, float *x_out, const float *w_in, float *w_out, float *z_out,
@@ -31,7 +17,6 @@ int cx_pushsum_mix(const float *x_in, float *x_out, const float *w_in, float *w_
         if (any_overlap(z_out, x_in, bytes) || any_overlap(z_out, x_out, bytes)) return CX_ERR_ALIAS;
     }
     const hipStream_t st = static_cast<hipStream_t>(stream);
-    // the de-biasing reads w_in, so the weights are written by their own tiny launch
     hipLaunchKernelGGL(pushsum_weight_kernel, dim3(1), dim3(256), 0, st, w_in, w_out, W, hop);
     if (hipGetLastError() != hipSuccess) return CX_ERR_HIP;
     const PushOp op{x_in, x_out, z_out, w_in, ld, W, hop};

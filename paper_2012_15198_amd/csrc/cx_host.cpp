@@ -97,7 +97,7 @@ const char *cx_status_string(int status)
     }
 }
 
-int cx_abi_version(void) { return 3; }
+int cx_abi_version(void) { return 4; }
 
 int cx_topology_gen(uint64_t seed, int32_t n, int32_t S, int32_t round0, int32_t R,
                     int32_t mode, int32_t *peers_host)

@@ -612,29 +612,35 @@ struct Row16Op {
                 }
         }
     }
-    template <int U, bool FULL, bool NT>
-    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
+    // fp32 values of a tile -> packed 16-bit pairs, round-to-nearest-even in hardware
+    template <int U>
+    static __device__ __forceinline__ void pack(const Tile<2 * U> &t, Tile<U> &packed)
     {
         typedef unsigned u4 __attribute__((ext_vector_type(4)));
         typedef float f2 __attribute__((ext_vector_type(2)));
         typedef __bf16 b2 __attribute__((ext_vector_type(2)));
         typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-        Tile<U> packed;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if constexpr (G == 1) {
-                u4 w;
+            u4 w;
 #pragma unroll
-                for (int pair = 0; pair < 4; ++pair) {
-                    // two fp32 -> one packed 16-bit pair, round-to-nearest-even in hardware
-                    const f2 two = {t.v[2 * u + (pair >> 1)][2 * (pair & 1)], t.v[2 * u + (pair >> 1)][2 * (pair & 1) + 1]};
-                    if constexpr (IEEE_HALF) w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, h2));
-                    else w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
-                }
-                packed.v[u] = __builtin_bit_cast(f4, w);
-            } else {
-                packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
+            for (int pair = 0; pair < 4; ++pair) {
+                const f2 two = {t.v[2 * u + (pair >> 1)][2 * (pair & 1)], t.v[2 * u + (pair >> 1)][2 * (pair & 1) + 1]};
+                if constexpr (IEEE_HALF) w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, h2));
+                else w[pair] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, b2));
             }
+            packed.v[u] = __builtin_bit_cast(f4, w);
+        }
+    }
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Work<U> &t) const
+    {
+        Tile<U> packed;
+        if constexpr (G == 1) {
+            pack<U>(t, packed);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) packed.v[u] = narrow16_once<IEEE_HALF>(t.v[2 * u], t.v[2 * u + 1]);
         }
         uint16_t *p = xout + static_cast<int64_t>(row) * G * ld + off;
 #pragma unroll
@@ -644,6 +650,35 @@ struct Row16Op {
 
 using Bf16Op = Row16Op<false>;
 using Fp16Op = Row16Op<true>;
+
+// The SGP-style push-sum comparison on 16-bit rows (PushOp below is the fp32-row one): the rows are widened
+// exactly, averaged in fp32 like Row16Op's, and the de-biased copy z = average / w' is the quotient of the
+// UNROUNDED fp32 average, narrowed once like x'.  The weights stay fp32.
+template <bool IEEE_HALF>
+struct Push16Op : Row16Op<IEEE_HALF, 1> {
+    using Base = Row16Op<IEEE_HALF, 1>;
+    static constexpr GatherShape kGather{2, 4, 192, 0};    // measured on C4: one slice per lane 52 %, two 76 %
+    static constexpr WalkShape kWalk{1, 2, 8, 0};
+    uint16_t *zout;       // may be null
+    const float *win;
+    int n, hop;
+
+    template <int U, bool FULL, bool NT>
+    __device__ __forceinline__ void store(int row, int64_t off, const unsigned (&mask)[U], const Tile<2 * U> &t) const
+    {
+        Base::template store<U, FULL, NT>(row, off, mask, t);
+        if (zout) {
+            const int from = row >= hop ? row - hop : row - hop + n;
+            const float wn = (win[row] + win[from]) * 0.5f;
+            Tile<2 * U> z;
+#pragma unroll
+            for (int u = 0; u < 2 * U; ++u) z.v[u] = t.v[u] / wn;
+            Tile<U> packed;
+            Base::template pack<U>(z, packed);
+            tile_store16<U, FULL, NT>(zout + static_cast<int64_t>(row) * this->ld + off, mask, packed);
+        }
+    }
+};
 
 // ---------------------------------------------------------------------------------
 // The optimizer operators on 16-bit rows: parameters and gradients are 16-bit (8 columns per
@@ -902,6 +937,17 @@ struct PushOp {
         }
     }
 };
+
+// w_out[i] = (w_in[i] + w_in[(i - hop) mod n]) * 0.5f  (push-sum weights, n <= CX_MAX_ROWS): the de-biasing in
+// PushOp / Push16Op reads w_in, so the new weights are written by their own tiny launch
+[[maybe_unused]] __global__ void pushsum_weight_kernel(const float *__restrict__ w_in, float *__restrict__ w_out,
+                                                       int n, int hop)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        const int from = i >= hop ? i - hop : i - hop + n;
+        w_out[i] = (w_in[i] + w_in[from]) * 0.5f;
+    }
+}
 
 // The two groups that build schedules: one wavefront in its private LDS region, or a workgroup.
 struct WaveSync {

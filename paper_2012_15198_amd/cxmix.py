@@ -31,6 +31,7 @@ EXPORTS = ["cx_status_string", "cx_abi_version", "cx_topology_gen", "cx_check_se
            "cx_check_peers", "cx_gossip_mix", "cx_hier_mix", "cx_pushsum_mix",
            "cx_sgd_fused_mix", "cx_hier_sgd_fused_mix", "cx_gossip_mix_noalloc", "cx_gossip_mix_bf16", "cx_gossip_mix_f16", "cx_hier_mix_bf16", "cx_hier_mix_f16",
            "cx_sgd_fused_mix_bf16", "cx_sgd_fused_mix_f16", "cx_hier_sgd_fused_mix_bf16", "cx_hier_sgd_fused_mix_f16",
+           "cx_pushsum_mix_bf16", "cx_pushsum_mix_f16",
            "cx_hbm_alloc", "cx_hbm_free", "cx_copy_baseline", "cx_set_tuning",
            "cx_get_tuning"]
 
@@ -85,6 +86,8 @@ def lib() -> ctypes.CDLL:
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, vp, vp, u32, vp]
     for name in ("cx_hier_sgd_fused_mix_bf16", "cx_hier_sgd_fused_mix_f16"):
         getattr(L, name).argtypes = [vp, vp, vp, vp, vp, f32, f32, f32, i64, i32, i64, i32, i32, vp, vp, u32, vp]
+    for name in ("cx_pushsum_mix_bf16", "cx_pushsum_mix_f16"):
+        getattr(L, name).argtypes = [vp, vp, vp, vp, vp, i64, i32, i64, i32, u32, vp]
     L.cx_hbm_alloc.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(i64), i32, u32]
     L.cx_hbm_free.argtypes = [vp]
     L.cx_copy_baseline.argtypes = [vp, vp, i64, vp]
@@ -303,6 +306,30 @@ def cx_pushsum_mix(x_in, x_out, w_in, w_out, z_out, P: int, hop: int, flags: int
     _ok("cx_pushsum_mix", lib().cx_pushsum_mix(_dptr(x_in), _dptr(x_out), _dptr(w_in),
                                                _dptr(w_out), _dptr(z_out), ld, W, P, hop, flags,
                                                _stream(stream)))
+
+
+def _pushsum16(name, x_in, x_out, w_in, w_out, z_out, P, hop, flags, stream):
+    W, ld = _shape(x_in, 2)
+    _matrix("x_out", x_out, W, ld, 2)
+    if z_out is not None:
+        _matrix("z_out", z_out, W, ld, 2)
+    _vector("w_in", w_in, W, 4)
+    _vector("w_out", w_out, W, 4)
+    if P < 1 or P > x_in.shape[1]:
+        raise ValueError("P must lie in [1, row length]")
+    _same_device(x_in, x_out, w_in, w_out, z_out)
+    _ok(name, getattr(lib(), name)(_dptr(x_in), _dptr(x_out), _dptr(w_in), _dptr(w_out), _dptr(z_out), ld, W, P, hop,
+                                   flags, _stream(stream)))
+
+
+def cx_pushsum_mix_bf16(x_in, x_out, w_in, w_out, z_out, P: int, hop: int, flags: int = 0, stream=None):
+    """x, z: torch.bfloat16 (or int16 bit patterns) [W][ld]; w: float32 [W]."""
+    _pushsum16("cx_pushsum_mix_bf16", x_in, x_out, w_in, w_out, z_out, P, hop, flags, stream)
+
+
+def cx_pushsum_mix_f16(x_in, x_out, w_in, w_out, z_out, P: int, hop: int, flags: int = 0, stream=None):
+    """x, z: torch.float16 (or int16 bit patterns) [W][ld]; w: float32 [W]."""
+    _pushsum16("cx_pushsum_mix_f16", x_in, x_out, w_in, w_out, z_out, P, hop, flags, stream)
 
 
 def cx_sgd_fused_mix(x_in, x_out, v_in, v_out, g, lr: float, mu: float, wd: float, P: int,

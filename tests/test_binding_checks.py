@@ -81,6 +81,10 @@ def test_16bit_entry_points_refuse_other_element_sizes():
     so2, pe2 = tables(W // G)
     refuses(cx.cx_hier_mix_bf16, b(), mat(), P, G, so2, pe2, match="16-bit")
     refuses(cx.cx_gossip_mix, b(), b(), P, so, pe, match="float32")
+    refuses(cx.cx_pushsum_mix_bf16, b(), mat(), torch.ones(W), torch.ones(W), None, P, 1, match="16-bit")
+    refuses(cx.cx_pushsum_mix_f16, b(), b(), torch.ones(W), torch.ones(W), mat(), P, 1, match="16-bit")
+    refuses(cx.cx_pushsum_mix_bf16, b(), b(), torch.ones(W - 1), torch.ones(W), None, P, 1, match="w_in")
+    refuses(cx.cx_pushsum_mix, b(), b(), torch.ones(W), torch.ones(W), None, P, 1, match="float32")
 
 
 def test_tables_and_vectors_are_checked():

@@ -22,7 +22,7 @@ def test_library_exports_every_symbol_the_header_declares():
     L = cx.lib()
     for name in declared:
         assert hasattr(L, name), name
-    assert cx.cx_abi_version() == 3
+    assert cx.cx_abi_version() == 4
     assert cx.cx_status_string(0) == "CX_OK" and cx.cx_status_string(-6) == "CX_ERR_ALIAS"
     for code, name in cx.STATUS.items():
         assert cx.cx_status_string(code) == name
@@ -212,6 +212,15 @@ def test_mix_calls_reject_bad_arguments_on_the_host():
     assert fused16(L.cx_hier_sgd_fused_mix_f16, True, G=3) == -2 and fused16(L.cx_hier_sgd_fused_mix_f16, True, pe=None) == -1
     assert fused16(L.cx_hier_sgd_fused_mix_bf16, True, G=16, W=32) == -8
 
+    for fn in (L.cx_pushsum_mix_bf16, L.cx_pushsum_mix_f16):
+        def push16(hop=1, w_in=C, w_out=D, z=None, **kw):
+            a = {**ok, **kw}
+            return fn(a["x_in"], a["x_out"], w_in, w_out, z, a["ld"], a["W"], a["P"], hop, a["flags"], a["st"])
+        assert push16(hop=0) == -2 and push16(hop=4) == -2 and push16(w_in=None) == -1 and push16(x_out=None) == -1
+        assert push16(ld=60, P=60) == -5 and push16(ld=56) == -2 and push16(flags=1) == -8
+        assert push16(w_out=C) == -6 and push16(z=A) == -6 and push16(z=B) == -6 and push16(z=E + 4) == -5
+        assert push16(x_out=A + 32) == -6
+
     assert L.cx_copy_baseline(None, B, 64, None) == -1
     assert L.cx_copy_baseline(A, B, 6, None) == -2
     assert L.cx_copy_baseline(A, A + 64, 64, None) == -6
@@ -267,7 +276,7 @@ int main(void)
     int32_t peers[R * S * N];
     int64_t seg_off[S + 1] = {0, 10, 20, 30};
     int r, s, i, rc;
-    if (cx_abi_version() != 3) return 10;
+    if (cx_abi_version() != 4) return 10;
     rc = cx_topology_gen(2u, N, S, 0, R, CX_TOPO_FAIR, peers);
     if (rc != CX_OK) return 11;
     for (r = 0; r < R; ++r)
