@@ -14,8 +14,8 @@ SOURCES = [os.path.join(CSRC, f) for f in ("cx_host.cpp", "cx_hbm.cpp", "cx_api_
                                            "cx_api_pushsum.hip", "cx_api_fused.hip", "cx_api_hiersgd.hip",
                                            "cx_api_bf16.hip", "cx_api_f16.hip", "cx_api_hier16.hip",
                                            "cx_api_noalloc.hip", "cx_api_fused16.hip", "cx_api_pushsum16.hip")]
-HEADERS = [os.path.join(ROOT, "include", "cx_mix.h"), os.path.join(CSRC, "cx_kernels.hpp"),
-           os.path.join(CSRC, "cx_schedule.hpp")]
+HEADERS = [os.path.join(ROOT, "include", "cx_mix.h")] + [os.path.join(CSRC, h) for h in (
+    "cx_schedule.hpp", "cx_tile.hpp", "cx_ops.hpp", "cx_ops16.hpp", "cx_kernels.hpp", "cx_launch.hpp")]
 OBJDIR = os.path.join(HERE, "_build")
 
 HIPCC_FLAGS = [

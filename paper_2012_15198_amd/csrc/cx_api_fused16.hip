@@ -1,6 +1,6 @@
 // C-ABI entry points cx_sgd_fused_mix_bf16 / _f16 and cx_hier_sgd_fused_mix_bf16 / _f16: argument
 // checks and launch (see include/cx_mix.h).
-#include "cx_kernels.hpp"
+#include "cx_launch.hpp"
 
 namespace {
 

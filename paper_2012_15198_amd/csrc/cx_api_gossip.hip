@@ -1,5 +1,5 @@
 // C-ABI entry point(s) cx_gossip_mix, cx_copy_baseline: argument checks and launch (see include/cx_mix.h).
-#include "cx_kernels.hpp"
+#include "cx_launch.hpp"
 
 namespace {
 

@@ -1,5 +1,5 @@
 // C-ABI entry point(s) cx_hier_mix: argument checks and launch (see include/cx_mix.h).
-#include "cx_kernels.hpp"
+#include "cx_launch.hpp"
 
 extern "C" {
 

@@ -2,7 +2,7 @@
 // include/cx_mix.h).  Its only scratch -- the row-order table that order_kernel writes and
 // gather_kernel reads -- is a file-scope device array of a fixed size; the kernels receive its
 // device address as an argument.
-#include "cx_kernels.hpp"
+#include "cx_launch.hpp"
 
 namespace {
 

@@ -1,5 +1,5 @@
 // C-ABI entry points cx_pushsum_mix_bf16, cx_pushsum_mix_f16: argument checks and launch (see include/cx_mix.h).
-#include "cx_kernels.hpp"
+#include "cx_launch.hpp"
 
 namespace {
 
