@@ -335,3 +335,33 @@ def test_c4_pushsum_sampled_all_rounds():
         if r == 6:      # after log2(W) = 7 exponential hops every row holds the exact mean
             assert np.abs(take(x, cold) - mean).max() <= 1e-6 * np.abs(mean).max() + 1e-7
     free(x, x2, z)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_c4_pushsum_on_16bit_rows_sampled_all_rounds(fmt):
+    """The push-sum comparison on 16-bit rows at C4's size, rounds alternating out of place and in place: x' and z
+    on the column sample, bit for bit against the oracle's 16-bit round, unit weights throughout."""
+    wl = WL.WORKLOADS["C4"]
+    ld = padded(wl.P)
+    dt = torch.bfloat16 if fmt == "bf16" else torch.float16
+    push = cx.cx_pushsum_mix_bf16 if fmt == "bf16" else cx.cx_pushsum_mix_f16
+    shifts = cx.cx_topology_gen(wl.seed, wl.W, 1, 0, wl.rounds, 1)
+    x = WL.gen_matrix_device(wl.W, wl.P, wl.sigma, wl.seed, ld=ld).to(dt)
+    x2, z = torch.empty_like(x), torch.empty_like(x)
+    cols, _, cold = sample(wl, np.array([0, wl.P]))
+    grab16 = lambda t: host(t.view(torch.int16).index_select(1, cold)).view(np.uint16)
+    sx = grab16(x)
+    sw = np.ones(wl.W, dtype=np.float32)
+    w0, w1 = torch.ones(wl.W, device=x.device), torch.zeros(wl.W, device=x.device)
+    for r in range(wl.rounds):
+        hop = int((0 - int(shifts[r, 0, 0])) % wl.W)
+        if r % 2 == 0:
+            push(x, x2, w0, w1, z, wl.P, hop)
+            x, x2 = x2, x
+        else:
+            push(x, x, w0, w1, z, wl.P, hop)
+        w0, w1 = w1, w0
+        sx, sw, sz = O.pushsum_mix16(fmt, sx, sw, len(cols), hop, True)
+        assert (grab16(x) == sx).all() and (grab16(z) == sz).all(), r
+        assert (host(w0) == 1.0).all()
+    free(x, x2, z)
