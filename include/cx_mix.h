@@ -345,7 +345,7 @@ int cx_pushsum_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float *w_in,
  * above.  Not an operation of the paper: it exists because WHERE a matrix lies in physical
  * memory sets the rate of the kernels that write many rows at once (the hierarchical mix of
  * Section 3.3, the in-place walk), and a caller cannot place memory with hipMalloc.  Measured
- * on MI355X: the 288 GiB act as three zones of 96 GiB of physical addresses; the hierarchical
+ * on MI355X (not on every machine alike): the 288 GiB act as three zones of 96 GiB of physical addresses; the hierarchical
  * mix at W = 256 runs at 67-69 % of the HBM peak when the buffer it writes lies in the zone of
  * the buffer it reads, at 73 % into another zone, at 77-78 % when both are spread over two
  * or three zones.  Buffers that hipMalloc returns one after the other mostly share a zone.

@@ -3,13 +3,14 @@
 // matrix lies in physical memory decides how fast the mixing kernels of Sections 3 and 3.3 write
 // it on this GPU, and a caller cannot place memory with hipMalloc.
 //
-// What is known, from measurement: the 288 GiB of an MI355X behave as three zones of 96 GiB of
-// physical addresses.  A kernel that writes many rows at once (the hierarchical mix writes the
-// eight rows of a group per workgroup, the in-place walk wanders over all rows) runs at 67-69 %
-// of the HBM peak into a buffer that lies in the zone of the buffer it reads, at 73 % into
-// another zone, and at 77-78 % when each buffer is spread over two or three zones -- whatever
-// the virtual addresses are.  hipMalloc hands out physical memory in address order, so two
-// buffers allocated one after the other mostly share a zone.
+// What is known, from measurement: on the machines where it shows, the 288 GiB of an MI355X behave
+// as three zones of 96 GiB of physical addresses.  A kernel that writes many rows at once (the
+// hierarchical mix writes the eight rows of a group per workgroup, the in-place walk wanders over
+// all rows) runs at 67-69 % of the HBM peak into a buffer that lies in the zone of the buffer it
+// reads, at 73 % into another zone, and at 77-78 % when each buffer is spread over two or three
+// zones -- whatever the virtual addresses are.  In a fresh process hipMalloc hands out physical
+// memory in address order, so two buffers allocated one after the other mostly share a zone; on
+// other machines of the same kind plain buffers lie well by themselves, and spreading costs nothing.
 //
 // What this file does about it: it takes the free memory of the device in the order the driver
 // hands it out (block chunks separated by fillers that stand for the memory skipped), so that
