@@ -361,7 +361,8 @@ int cx_pushsum_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float *w_in,
  *   given back.  Meant for start-up, not for a loop.  Thread-safe.
  *   The pointers are ordinary device pointers for every call of this header, for kernels and
  *   hipMemcpy; they are NOT hipMalloc pointers: release each with cx_hbm_free, never hipFree.
- *   cx_hbm_free waits for the block's device to go idle, then unmaps the block.
+ *   cx_hbm_free waits for the block's device to go idle (hipDeviceSynchronize: not while a
+ *   stream of that device is capturing a graph), then unmaps the block.
  * Errors: CX_ERR_NULL; CX_ERR_SHAPE if count < 1, count > 64 or a size < 1; CX_ERR_UNSUPPORTED
  * if flags != 0, and from cx_hbm_free for a pointer that is not a live block of cx_hbm_alloc;
  * CX_ERR_MEMORY if the device has less free memory than asked for; CX_ERR_HIP if the runtime
