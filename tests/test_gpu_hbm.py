@@ -75,3 +75,31 @@ def test_mix_on_placed_tensors_matches_the_oracle_and_plain_tensors():
     del row
     gc.collect()
     assert torch.cuda.mem_get_info()[0] >= free_before + 4 * W * ld * 2 - 64 * MiB
+
+
+def test_placement_on_a_nearly_full_device():
+    """Most of the memory held by somebody else (torch): the call still serves what fits -- with little or
+    nothing left to skip -- says CX_ERR_MEMORY for what does not, and gives everything back."""
+    torch.cuda.empty_cache()
+    free0 = torch.cuda.mem_get_info()[0]
+    keep = 24 << 30
+    if free0 < keep + (8 << 30):
+        pytest.skip("not enough free memory to stage the case")
+    hog = torch.empty(free0 - keep, dtype=torch.uint8, device="cuda:0")
+    try:
+        free1 = torch.cuda.mem_get_info()[0]
+        assert free1 <= keep + (1 << 30)
+        with pytest.raises(cx.CxError, match="CX_ERR_MEMORY"):
+            cx.cx_hbm_alloc([free1 + (64 << 20)])
+        assert abs(torch.cuda.mem_get_info()[0] - free1) <= 64 * MiB          # nothing kept after the refusal
+        a, b = cx.hbm_empty([(4, 1 << 28), (4, 1 << 28)])                       # 2 x 4 GiB of float32
+        a.fill_(1.0)
+        b.fill_(3.0)
+        assert float(a.min()) == 1.0 and float(a.max()) == 1.0 and float(b.min()) == 3.0 and float(b.max()) == 3.0
+        del a, b
+        gc.collect()
+        torch.cuda.empty_cache()
+        assert abs(torch.cuda.mem_get_info()[0] - free1) <= 256 * MiB
+    finally:
+        del hog
+        torch.cuda.empty_cache()
