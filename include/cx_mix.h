@@ -193,7 +193,7 @@ int cx_gossip_mix_noalloc(const float *x_in, float *x_out, int64_t ld, int32_t W
  * leader_peers_dev is int32 [S][L] (may be NULL when L == 1: the result is then the
  * global mean, i.e. the AllReduce mixing matrix).
  * Errors: as cx_gossip_mix, plus CX_ERR_SHAPE if G < 1, W % G != 0 or L > CX_MAX_ROWS;
- * CX_ERR_UNSUPPORTED if G is not one of 1, 2, 4, 8, 16.
+ * CX_ERR_UNSUPPORTED if G is not one of 1 ... 8, 16.
  */
 int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t P,
                 int32_t G, int32_t S, const int64_t *seg_off_dev,
@@ -247,7 +247,7 @@ int cx_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *
  * x_out may equal x_in and v_out may equal v_in (then both must); with L == 1 this is
  * AllReduce-SGD.  Per worker-parameter it moves 8 + 12/G bytes (read g, write x; the leader
  * also reads x, v and writes v).
- * Errors: as cx_hier_mix (group sizes 1, 2, 4, 8, 16); CX_ERR_ALIAS also if exactly one of x, v is
+ * Errors: as cx_hier_mix (group sizes 1 ... 8, 16); CX_ERR_ALIAS also if exactly one of x, v is
  * updated in place, or v overlaps x or g.
  */
 int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, float *v_out,
@@ -283,7 +283,7 @@ int cx_gossip_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t
  * [W][ld] of bfloat16 / binary16 bit patterns, ld % 8 == 0.  Every value is widened exactly, the
  * group sum, the division by G and the leader average run in fp64 as in cx_hier_mix, and the result
  * is rounded ONCE (nearest even, straight from the fp64 value) before it is written to the G rows of
- * the group.  G = 1, 2, 4, 8 (CX_ERR_UNSUPPORTED otherwise); G = 1 is cx_gossip_mix_bf16 / _f16 (and
+ * the group.  G = 1 ... 8 (CX_ERR_UNSUPPORTED otherwise); G = 1 is cx_gossip_mix_bf16 / _f16 (and
  * needs W >= 2).  Everything else as cx_hier_mix.
  */
 int cx_hier_mix_bf16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int64_t P,
@@ -303,7 +303,7 @@ int cx_hier_mix_f16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W
  * straight from the fp64 value: not through fp32, which could land on the wrong side of a tie).
  * Bytes per worker-parameter: 14 (flat: read x, g, v; write x, v) and 4 + 10/G (hierarchical).
  * x and v are updated either both in place or both out of place (CX_ERR_ALIAS otherwise, and
- * for any other overlap between x, v and g).  Hierarchical group sizes: 1, 2, 4, 8.
+ * for any other overlap between x, v and g).  Hierarchical group sizes: 1 ... 8.
  * Everything else as cx_sgd_fused_mix and cx_hier_sgd_fused_mix.
  */
 int cx_sgd_fused_mix_bf16(const uint16_t *x_in, uint16_t *x_out, const float *v_in, float *v_out,

@@ -63,7 +63,11 @@ int hier_fused16(const uint16_t *x_in, uint16_t *x_out, const float *v_in, float
     switch (G) {
     case 1: return launch_mix<HierFused16Op<IEEE_HALF, 1>>(HierFused16Op<IEEE_HALF, 1>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     case 2: return launch_mix<HierFused16Op<IEEE_HALF, 2>>(HierFused16Op<IEEE_HALF, 2>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 3: return launch_mix<HierFused16Op<IEEE_HALF, 3>>(HierFused16Op<IEEE_HALF, 3>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     case 4: return launch_mix<HierFused16Op<IEEE_HALF, 4>>(HierFused16Op<IEEE_HALF, 4>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 5: return launch_mix<HierFused16Op<IEEE_HALF, 5>>(HierFused16Op<IEEE_HALF, 5>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 6: return launch_mix<HierFused16Op<IEEE_HALF, 6>>(HierFused16Op<IEEE_HALF, 6>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 7: return launch_mix<HierFused16Op<IEEE_HALF, 7>>(HierFused16Op<IEEE_HALF, 7>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     case 8: return launch_mix<HierFused16Op<IEEE_HALF, 8>>(HierFused16Op<IEEE_HALF, 8>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     default: return CX_ERR_UNSUPPORTED;
     }

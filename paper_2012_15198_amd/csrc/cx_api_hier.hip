@@ -21,7 +21,11 @@ int cx_hier_mix(const float *x_in, float *x_out, int64_t ld, int32_t W, int64_t 
     switch (G) {
     case 1: return launch_mix<MeanOp<1>>(MeanOp<1>{x_in, x_out, ld}, a);
     case 2: return launch_mix<MeanOp<2>>(MeanOp<2>{x_in, x_out, ld}, a);
+    case 3: return launch_mix<MeanOp<3>>(MeanOp<3>{x_in, x_out, ld}, a);
     case 4: return launch_mix<MeanOp<4>>(MeanOp<4>{x_in, x_out, ld}, a);
+    case 5: return launch_mix<MeanOp<5>>(MeanOp<5>{x_in, x_out, ld}, a);
+    case 6: return launch_mix<MeanOp<6>>(MeanOp<6>{x_in, x_out, ld}, a);
+    case 7: return launch_mix<MeanOp<7>>(MeanOp<7>{x_in, x_out, ld}, a);
     case 8:
         // launch parameter 10: the group mean staged through LDS (one row per wavefront) instead of the
         // sum in registers -- same results, kept so that the two can be measured side by side

@@ -25,7 +25,11 @@ int hier_mix16(const uint16_t *x_in, uint16_t *x_out, int64_t ld, int32_t W, int
     const MixArgs a{L, P, S, seg_off_dev, peers, 0, skip, st, x_in != x_out, G};
     switch (G) {
     case 2: return launch_mix<Row16Op<IEEE_HALF, 2>>(Row16Op<IEEE_HALF, 2>{x_in, x_out, ld}, a);
+    case 3: return launch_mix<Row16Op<IEEE_HALF, 3>>(Row16Op<IEEE_HALF, 3>{x_in, x_out, ld}, a);
     case 4: return launch_mix<Row16Op<IEEE_HALF, 4>>(Row16Op<IEEE_HALF, 4>{x_in, x_out, ld}, a);
+    case 5: return launch_mix<Row16Op<IEEE_HALF, 5>>(Row16Op<IEEE_HALF, 5>{x_in, x_out, ld}, a);
+    case 6: return launch_mix<Row16Op<IEEE_HALF, 6>>(Row16Op<IEEE_HALF, 6>{x_in, x_out, ld}, a);
+    case 7: return launch_mix<Row16Op<IEEE_HALF, 7>>(Row16Op<IEEE_HALF, 7>{x_in, x_out, ld}, a);
     case 8: return launch_mix<Row16Op<IEEE_HALF, 8>>(Row16Op<IEEE_HALF, 8>{x_in, x_out, ld}, a);
     default: return CX_ERR_UNSUPPORTED;
     }

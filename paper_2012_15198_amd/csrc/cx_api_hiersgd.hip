@@ -37,7 +37,11 @@ int cx_hier_sgd_fused_mix(const float *x_in, float *x_out, const float *v_in, fl
     switch (G) {
     case 1: return launch_mix<HierFusedOp<1>>(HierFusedOp<1>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     case 2: return launch_mix<HierFusedOp<2>>(HierFusedOp<2>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 3: return launch_mix<HierFusedOp<3>>(HierFusedOp<3>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     case 4: return launch_mix<HierFusedOp<4>>(HierFusedOp<4>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 5: return launch_mix<HierFusedOp<5>>(HierFusedOp<5>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 6: return launch_mix<HierFusedOp<6>>(HierFusedOp<6>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
+    case 7: return launch_mix<HierFusedOp<7>>(HierFusedOp<7>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     case 8: return launch_mix<HierFusedOp<8>>(HierFusedOp<8>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     case 16: return launch_mix<HierFusedOp<16>>(HierFusedOp<16>{x_in, x_out, v_in, v_out, g, ld, sgd}, a);
     default: return CX_ERR_UNSUPPORTED;

@@ -133,7 +133,9 @@ def test_fused16_rounds_under_every_launch_shape(fmt, tuning):
 
 @pytest.mark.parametrize("fmt", ["bf16", "f16"])
 @pytest.mark.parametrize("W,G,P,ld,S", [(2, 2, 5, 8, 1), (4, 2, 13, 16, 2), (8, 1, 3001, 3008, 3), (8, 4, 9001, 9008, 4),
-                                        (64, 8, 4099, 4104, 16), (16, 8, 8195, 8320, 5), (8, 8, 2100, 2104, 3)])
+                                        (64, 8, 4099, 4104, 16), (16, 8, 8195, 8320, 5), (8, 8, 2100, 2104, 3),
+                                        (12, 3, 4099, 4104, 3), (20, 5, 3001, 3008, 2), (36, 6, 8195, 8320, 7),
+                                        (21, 7, 5003, 5008, 4), (3, 3, 1030, 1032, 1)])
 @pytest.mark.parametrize("inplace", [False, True])
 def test_hier_fused16_bit_exact(fmt, W, G, P, ld, S, inplace):
     L = W // G

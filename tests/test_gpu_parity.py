@@ -444,7 +444,9 @@ def _fmt16(fmt):
 @pytest.mark.parametrize("fmt", ["bf16", "f16"])
 @pytest.mark.parametrize("W,G,P,ld,S", [(2, 2, 5, 8, 1), (4, 2, 13, 16, 2), (8, 1, 3001, 3008, 3), (8, 4, 9001, 9008, 4),
                                         (16, 8, 8195, 8320, 7), (24, 8, 5003, 5008, 5), (64, 8, 3000, 3000, 5),
-                                        (32, 4, 4100, 4104, 3), (8, 8, 2500, 2504, 2)])
+                                        (32, 4, 4100, 4104, 3), (8, 8, 2500, 2504, 2),
+                                        (12, 3, 4099, 4104, 3), (20, 5, 3001, 3008, 2), (36, 6, 8195, 8320, 7),
+                                        (21, 7, 5003, 5008, 4), (7, 7, 2100, 2104, 2)])
 @pytest.mark.parametrize("inplace", [False, True])
 def test_hier16_bit_exact(fmt, W, G, P, ld, S, inplace):
     mix, narrow, same = _fmt16(fmt)
@@ -498,7 +500,9 @@ def hier_want(x, P, G, so, pe):
 
 @pytest.mark.parametrize("W,G,P,ld,S", [(8, 1, 3001, 3004, 3), (8, 2, 3001, 3004, 3), (16, 4, 5003, 5004, 4),
                                         (64, 8, 4099, 4100, 16), (32, 16, 2600, 2600, 2),
-                                        (8, 8, 2100, 2100, 3), (16, 16, 1030, 1032, 1), (2, 2, 5, 8, 1)])
+                                        (8, 8, 2100, 2100, 3), (16, 16, 1030, 1032, 1), (2, 2, 5, 8, 1),
+                                        (12, 3, 4099, 4100, 3), (20, 5, 3001, 3004, 2), (36, 6, 8195, 8196, 7),
+                                        (21, 7, 5003, 5004, 4), (6, 6, 1030, 1032, 1)])
 @pytest.mark.parametrize("inplace", [False, True])
 def test_hier_is_the_fp64_reference_rounded_once(W, G, P, ld, S, inplace):
     x = WL.gen_matrix(W, P, 0.05, seed=W + G + P, ld=ld)
@@ -655,7 +659,8 @@ def test_fused_lr0_is_gossip_and_rounds_track_oracle():
 # ------------------------------------------------ hierarchical step with gradients (Section 3.3)
 @pytest.mark.parametrize("W,G,P,ld,S", [(4, 1, 2100, 2100, 2), (8, 2, 3001, 3004, 3), (16, 4, 5003, 5004, 4),
                                         (64, 8, 4099, 4100, 16), (8, 8, 2100, 2100, 3), (2, 2, 5, 8, 1),
-                                        (64, 16, 3001, 3004, 3)])
+                                        (64, 16, 3001, 3004, 3), (12, 3, 4099, 4100, 3), (20, 5, 3001, 3004, 2),
+                                        (36, 6, 8195, 8196, 7), (21, 7, 5003, 5004, 4), (5, 5, 1030, 1032, 1)])
 @pytest.mark.parametrize("inplace", [False, True])
 def test_hier_sgd_fused_is_the_fp64_reference_rounded_once(W, G, P, ld, S, inplace):
     lr, mu, wd = 0.1, 0.9, 1e-4
