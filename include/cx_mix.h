@@ -353,6 +353,8 @@ int cx_pushsum_mix_f16(const uint16_t *x_in, uint16_t *x_out, const float *w_in,
  *   current device: every block is assembled from 256 MiB pieces of physical memory that lie
  *   evenly over all the memory that is free when the call starts, mapped to one virtual range
  *   (2 MiB aligned), readable and writable by that device only.  Contents are unspecified.
+ *   (CX_HBM_PIECE_MIB in the environment, an even number from 2 to 1024, sets another piece
+ *   size: a knob for measurements; 16, 64 and 256 MiB measured alike.)
  *   ptrs_out[k] (host array of `count` pointers) receives the device addresses; on any error
  *   every entry is NULL and nothing stays allocated.  Blocks of one call interleave, so ask
  *   for the buffers of one job (x, x', v, v', g) in one call.

@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <map>
 #include <mutex>
 #include <vector>
@@ -28,7 +29,17 @@
 namespace {
 
 constexpr size_t kGranule = size_t{2} << 20;     // sizes and addresses are multiples of 2 MiB
-constexpr size_t kChunk = size_t{256} << 20;     // physical piece of a block
+constexpr size_t kDefaultPiece = size_t{256} << 20;   // physical piece of a block
+
+// CX_HBM_PIECE_MIB in the environment (an even number of MiB, 2 ... 1024) changes the piece size: for measurements
+size_t piece_bytes()
+{
+    if (const char *v = std::getenv("CX_HBM_PIECE_MIB")) {
+        const long mib = std::strtol(v, nullptr, 10);
+        if (mib >= 2 && mib <= 1024 && mib % 2 == 0) return static_cast<size_t>(mib) << 20;
+    }
+    return kDefaultPiece;
+}
 constexpr size_t kFiller = size_t{1} << 30;      // largest piece of skipped memory
 constexpr size_t kHeadroom = size_t{8} << 30;    // left untouched for everybody else while the call runs
 constexpr int kMaxBlocks = 64;
@@ -82,15 +93,16 @@ int cx_hbm_alloc(void **ptrs_out, const int64_t *bytes, int32_t count, uint32_t 
 
     // the chunks of all blocks, sorted by their position inside their block: created in this
     // order with equal fillers between them, every block's chunks end up evenly over the free memory
+    const size_t piece = piece_bytes();
     std::vector<Piece> pieces;
     for (int k = 0; k < count; ++k) {
-        const size_t n = (size[k] + kChunk - 1) / kChunk;
+        const size_t n = (size[k] + piece - 1) / piece;
         for (size_t c = 0; c < n; ++c) {
             Piece p;
             p.where = (static_cast<double>(c) + 0.5) / static_cast<double>(n);
             p.block = k;
-            p.offset = c * kChunk;
-            p.bytes = std::min(kChunk, size[k] - p.offset);
+            p.offset = c * piece;
+            p.bytes = std::min(piece, size[k] - p.offset);
             pieces.push_back(p);
         }
     }
@@ -104,15 +116,15 @@ int cx_hbm_alloc(void **ptrs_out, const int64_t *bytes, int32_t count, uint32_t 
     bool fill = gap > 0;
     for (Piece &p : pieces) {
         for (size_t done = 0; fill && done < gap;) {
-            const size_t piece = std::min(kFiller, gap - done);
+            const size_t skipped = std::min(kFiller, gap - done);
             hipMemGenericAllocationHandle_t h;
-            if (hipMemCreate(&h, piece, &prop, 0) != hipSuccess) {      // less was free than reported: stop skipping
+            if (hipMemCreate(&h, skipped, &prop, 0) != hipSuccess) {      // less was free than reported: stop skipping
                 (void)hipGetLastError();
                 fill = false;
                 break;
             }
             fillers.push_back(h);
-            done += piece;
+            done += skipped;
         }
         hipError_t made = hipMemCreate(&p.handle, p.bytes, &prop, 0);
         if (made != hipSuccess && !fillers.empty()) {
