@@ -208,7 +208,7 @@ struct FusedOp {
     template <int U> using Work = WideTile<U>;             // the updated row, in fp64
     static constexpr int kRawPerSlice = 3;
     static constexpr GatherShape kGather{1, 8, 128, 3};
-    static constexpr WalkShape kWalk{2, 2, 4, 2};
+    static constexpr WalkShape kWalk{2, 2, 8, 2};
     static constexpr int kMaxU = 2;                        // fp64 rows: two slices per lane fill the registers
     template <int U> struct Raw { Tile<U> x, v, g; };
     const float *xin;

@@ -201,7 +201,7 @@ struct Row16Op {
 using Bf16Op = Row16Op<false>;
 using Fp16Op = Row16Op<true>;
 
-// The SGP-style push-sum comparison on 16-bit rows (PushOp below is the fp32-row one): the rows are widened
+// The SGP-style push-sum comparison on 16-bit rows (PushOp in cx_ops.hpp is the fp32-row one): the rows are widened
 // exactly, averaged in fp32 like Row16Op's, and the de-biased copy z = average / w' is the quotient of the
 // UNROUNDED fp32 average, narrowed once like x'.  The weights stay fp32.
 template <bool IEEE_HALF>
