@@ -1,0 +1,242 @@
+"""A training loop's rounds captured once in a HIP graph and replayed, for every family of entry
+points: hierarchical mix (Section 3.3), fused SGD step then mix (Section 3.1), the gradient-reducing
+hierarchical step, the push-sum comparison, and the 16-bit rows of Section 4.1.  The calls only
+enqueue kernels -- no allocation, no memset -- so capture must record them as they are; every
+replay, with eager calls on the same stream between replays, must give the oracle's bits.  Small
+matrices take the natural row order by default: the row-order table, which a graph bakes into its
+kernel arguments, is switched on for the capture."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2012_15198_amd import cxmix as cx
+from paper_2012_15198_amd import workloads as WL
+from gpu_util import dev, host, same_bits
+
+pytestmark = pytest.mark.gpu
+
+R = 4                     # even: ping-pong results land in the first buffer again
+LR, MU, WD = 0.1, 0.9, 1e-4
+
+
+def once(a):
+    return a.astype(np.float32)
+
+
+def d16(a):
+    return dev(np.ascontiguousarray(a).view(np.int16))
+
+
+def h16(t):
+    return host(t).view(np.uint16)
+
+
+_SIDE = []
+
+
+def capture_stream():
+    """One capture stream for the whole file: graphs captured on one stream share one row-order table
+    per entry point, and these tests replay them one after the other."""
+    if not _SIDE:
+        _SIDE.append(torch.cuda.Stream())
+    return _SIDE[0]
+
+
+def replay_and_check(record, reset, check, eager):
+    """Warm up on the capture stream, capture record(), then three replays, each from reset state and
+    each followed by an eager call and its own check."""
+    side = capture_stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        record(side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    reset()
+    torch.cuda.synchronize()
+    cx.cx_set_tuning(cx.TUNE_ORDERED, 1)
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            record(None)
+    finally:
+        cx.cx_set_tuning(cx.TUNE_ORDERED, -1)
+    for replay in range(3):
+        reset()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check(replay)
+        eager(replay)
+
+
+def test_hierarchical_rounds_in_a_graph():
+    W, G, P, ld, S = 32, 8, 20011, 20016, 4
+    x = WL.gen_matrix(W, P, 1.0, seed=71, ld=ld)
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(71, W // G, S, 0, R)
+    want = x
+    for r in range(R):
+        want = once(O.hier_mix_f64(want, P, G, so, tabs[r]))
+    sod, tds, x0 = dev(so), [dev(t) for t in tabs], dev(x)
+    a, b, c = dev(x), dev(x), dev(x)
+
+    def record(stream):
+        p, q = a, b
+        for r in range(R):
+            cx.cx_hier_mix(p, q, P, G, sod, tds[r], stream=stream)
+            p, q = q, p
+            cx.cx_hier_mix(c, c, P, G, sod, tds[r], stream=stream)
+
+    def reset():
+        a.copy_(x0)
+        c.copy_(x0)
+
+    def check(replay):
+        assert same_bits(host(a), want) and same_bits(host(c), want), replay
+
+    def eager(replay):
+        cx.cx_hier_mix(x0, b, P, G, sod, tds[replay])
+        torch.cuda.synchronize()
+        assert same_bits(host(b), once(O.hier_mix_f64(x, P, G, so, tabs[replay])))
+
+    replay_and_check(record, reset, check, eager)
+
+
+@pytest.mark.parametrize("G", [1, 4])
+def test_optimizer_rounds_in_a_graph(G):
+    """G = 1: cx_sgd_fused_mix; G = 4: cx_hier_sgd_fused_mix (momentum rows for the leaders only)."""
+    W, P, ld, S = 16, 12007, 12008, 3
+    L = W // G
+    x = WL.gen_matrix(W, P, 0.05, seed=72, ld=ld)
+    v = np.zeros((L, ld), dtype=np.float32)
+    gs = [WL.gen_matrix(W, P, 0.01, seed=72, ld=ld, stream=10 + r) for r in range(R)]
+    so = WL.equal_seg_off(P, S)
+    tabs = O.topology(72, L, S, 0, R)
+
+    def oracle_step(xx, vv, g, tab):
+        if G == 1:
+            return tuple(once(t) for t in O.sgd_fused_mix_f64(xx, vv, g, LR, MU, WD, P, so, tab))
+        return tuple(once(t) for t in O.hier_sgd_fused_mix_f64(xx, vv, g, LR, MU, WD, P, G, so, tab))
+
+    def call(xi, xo, vi, vo, g, tab, stream=None):
+        if G == 1:
+            cx.cx_sgd_fused_mix(xi, xo, vi, vo, g, LR, MU, WD, P, sod, tab, stream=stream)
+        else:
+            cx.cx_hier_sgd_fused_mix(xi, xo, vi, vo, g, LR, MU, WD, P, G, sod, tab, stream=stream)
+
+    wx, wv = x, v
+    for r in range(R):
+        wx, wv = oracle_step(wx, wv, gs[r], tabs[r])
+    sod, tds, gds = dev(so), [dev(t) for t in tabs], [dev(g) for g in gs]
+    x0, v0 = dev(x), dev(v)
+    xa, xb, va, vb = dev(x), dev(x), dev(v), dev(v)
+    xc, vc = dev(x), dev(v)
+
+    def record(stream):
+        p, q, s, t = xa, xb, va, vb
+        for r in range(R):
+            call(p, q, s, t, gds[r], tds[r], stream)
+            p, q, s, t = q, p, t, s
+            call(xc, xc, vc, vc, gds[r], tds[r], stream)
+
+    def reset():
+        xa.copy_(x0)
+        va.copy_(v0)
+        xc.copy_(x0)
+        vc.copy_(v0)
+
+    def check(replay):
+        assert same_bits(host(xa), wx) and same_bits(host(va), wv), replay
+        assert same_bits(host(xc), wx) and same_bits(host(vc), wv), replay
+
+    def eager(replay):
+        call(x0, xb, v0, vb, gds[replay], tds[replay])
+        torch.cuda.synchronize()
+        ex, ev = oracle_step(x, v, gs[replay], tabs[replay])
+        assert same_bits(host(xb), ex) and same_bits(host(vb), ev)
+
+    replay_and_check(record, reset, check, eager)
+
+
+def test_pushsum_hops_in_a_graph():
+    """log2(W) hops of the exponential graph: rows, weights and the de-biased copy, all from the graph."""
+    W, P, ld = 16, 9001, 9004
+    x = WL.gen_matrix(W, P, 0.05, seed=73, ld=ld)
+    w = (1.0 + 0.5 * np.random.default_rng(73).random(W)).astype(np.float32)
+    wx, ww, wz = x, w, None
+    for k in range(R):
+        wx, ww, wz = O.pushsum_mix_f32(wx, ww, P, 2 ** k, True)
+    x0, w0 = dev(x), dev(w)
+    xa, xb = dev(x), dev(x)
+    wa, wb = dev(w), dev(w)
+    z = torch.zeros_like(xa)
+
+    def record(stream):
+        p, q, s, t = xa, xb, wa, wb
+        for k in range(R):
+            cx.cx_pushsum_mix(p, q, s, t, z, P, 2 ** k, stream=stream)
+            p, q, s, t = q, p, t, s
+
+    def reset():
+        xa.copy_(x0)
+        wa.copy_(w0)
+        z.zero_()
+
+    def check(replay):
+        assert same_bits(host(xa), wx) and same_bits(host(wa), ww), replay
+        assert same_bits(host(z)[:, :P], wz[:, :P]), replay
+
+    def eager(replay):
+        cx.cx_pushsum_mix(x0, xb, w0, wb, None, P, 2 ** replay)
+        torch.cuda.synchronize()
+        ex, ew, _ = O.pushsum_mix_f32(x, w, P, 2 ** replay, False)
+        assert same_bits(host(xb), ex) and same_bits(host(wb), ew)
+
+    replay_and_check(record, reset, check, eager)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_mixed_precision_rounds_in_a_graph(fmt):
+    """16-bit parameters and gradients, fp32 momentum: the fused step, then a hierarchical mix of the
+    result, per round -- two entry points on 16-bit rows in one captured schedule."""
+    W, G, P, ld, S = 16, 2, 10003, 10008, 3
+    narrow = O.f32_to_bf16 if fmt == "bf16" else O.f32_to_f16
+    fused = cx.cx_sgd_fused_mix_bf16 if fmt == "bf16" else cx.cx_sgd_fused_mix_f16
+    hier = cx.cx_hier_mix_bf16 if fmt == "bf16" else cx.cx_hier_mix_f16
+    x = narrow(WL.gen_matrix(W, P, 0.05, seed=74, ld=ld))
+    v = WL.gen_matrix(W, P, 0.02, seed=74, ld=ld, stream=1)
+    gs = [narrow(WL.gen_matrix(W, P, 0.01, seed=74, ld=ld, stream=10 + r)) for r in range(R)]
+    so = WL.equal_seg_off(P, S)
+    flat_tabs = O.topology(74, W, S, 0, R)
+    lead_tabs = O.topology(75, W // G, S, 0, R)
+    wx, wv = x, v
+    for r in range(R):
+        wx, wv = O.sgd_fused_mix16(fmt, wx, wv, gs[r], LR, MU, WD, P, so, flat_tabs[r])
+        wx = O.hier_mix16(fmt, wx, P, G, so, lead_tabs[r])
+    sod = dev(so)
+    fds, lds, gds = [dev(t) for t in flat_tabs], [dev(t) for t in lead_tabs], [d16(g) for g in gs]
+    x0, v0 = d16(x), dev(v)
+    xa, xb, va, vb = d16(x), d16(x), dev(v), dev(v)
+
+    def record(stream):
+        s, t = va, vb
+        for r in range(R):
+            fused(xa, xb, s, t, gds[r], LR, MU, WD, P, sod, fds[r], stream=stream)
+            hier(xb, xa, P, G, sod, lds[r], stream=stream)
+            s, t = t, s
+
+    def reset():
+        xa.copy_(x0)
+        va.copy_(v0)
+
+    def check(replay):
+        assert (h16(xa) == wx).all() and same_bits(host(va), wv), replay
+
+    def eager(replay):
+        fused(x0, xb, v0, vb, gds[replay], LR, MU, WD, P, sod, fds[replay])
+        torch.cuda.synchronize()
+        ex, ev = O.sgd_fused_mix16(fmt, x, v, gs[replay], LR, MU, WD, P, so, flat_tabs[replay])
+        assert (h16(xb) == ex).all() and same_bits(host(vb), ev)
+
+    replay_and_check(record, reset, check, eager)
