@@ -302,3 +302,23 @@ int main(void)
     want = cx.cx_topology_gen(2, 8, 3, 0, 1)[0]
     assert [list(map(int, r.split())) for r in rows[:3]] == want.tolist()
     assert rows[3] == cx.cx_status_string(-4)
+
+
+def test_topology_against_the_oracle_on_drawn_arguments():
+    """Seeds over the whole 64-bit range, odd rank counts, late rounds, every mode: the host generator
+    (a pool the draws index into) and the oracle (a scan over a taken[] array) must agree entry for
+    entry, and the table checker must accept what either wrote."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=200, deadline=None, derandomize=True)
+    @given(seed=st.integers(0, 2**64 - 1), n=st.integers(2, 70), S=st.integers(1, 5),
+           round0=st.integers(0, 2**31 - 8), R=st.integers(1, 3), mode=st.sampled_from([0, 1, 2, 16, 17, 18]))
+    def check(seed, n, S, round0, R, mode):
+        got = cx.cx_topology_gen(seed, n, S, round0, R, mode)
+        assert (got == O.topology(seed, n, S, round0, R, mode)).all()
+        for tab in got:
+            cx.cx_check_peers(tab, mode & 3)
+            if mode & cx.CX_TOPO_SAME_ALL_SEGMENTS:
+                assert (tab == tab[0]).all()
+
+    check()
