@@ -9,7 +9,7 @@ import torch
 import oracle as O
 from paper_2012_15198_amd import cxmix as cx
 from paper_2012_15198_amd import workloads as WL
-from gpu_util import dev, host, same_bits
+from gpu_util import Tuning, dev, host, same_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -179,3 +179,59 @@ def test_sixteen_bit_rows(case, fmt):
             torch.cuda.synchronize()
             assert (h16(xo) == wx).all() and same_bits(host(wo), ww), inplace
             assert (h16(z)[:, :P] == wz[:, :P]).all(), inplace
+
+
+def draw_tuning(rng):
+    """Launch parameters anywhere in their documented ranges (-1 = the operator's default)."""
+    pick = lambda values: int(rng.choice(values))
+    return Tuning(slices=pick([-1, 1, 2, 4]), waves=pick([-1, 1, 2, 3, 4, 5, 8]), nt=pick([-1, 0, 1]),
+                  depth=pick([-1, 2, 4, 8]), lockstep=pick([-1, 0, 1]), force_walk=pick([-1, 0, 0, 1]),
+                  cluster=pick([-1, 1, 2, 3, 7, 64, 4096]), xcd_aware=pick([-1, 0, 1]), ordered=pick([-1, 0, 1, 1]),
+                  wgs_per_cu=pick([-1, 0, 1, 2, 8, 16]), lds_mean=pick([-1, 0, 1]))
+
+
+@pytest.mark.parametrize("case", range(CASES))
+def test_drawn_shapes_under_drawn_launch_parameters(case):
+    """Shape and launch shape both drawn: flat or hierarchical mix (groups of 8 every third case, which
+    the LDS-staged mean serves), then the matching optimizer step, fp32 and bf16 rows."""
+    rng = np.random.default_rng(5000 + case)
+    W, G, P, ld, so = draw_shape(rng, 8, grouped=case % 2 == 1)
+    if case % 3 == 0:
+        L = int(rng.integers(2, 10))
+        W, G = 8 * L, 8
+    L = W // G
+    tune = draw_tuning(rng)
+    print(f"W={W} G={G} P={P} ld={ld} seg_off={so.tolist()} tuning={tune.v}", flush=True)
+    x = WL.gen_matrix(W, P, 0.05, seed=5000 + case, ld=ld)
+    v = WL.gen_matrix(L, P, 0.02, seed=5000 + case, ld=ld, stream=1)
+    g = WL.gen_matrix(W, P, 0.01, seed=5000 + case, ld=ld, stream=2)
+    x16, g16 = O.f32_to_bf16(x), O.f32_to_bf16(g)
+    pe = tables(case, L, len(so) - 1)
+    sod, ped = dev(so), tdev(pe)
+    if G == 1:
+        want = O.gossip_mix(x, P, so, pe)
+        want16 = O.gossip_mix_bf16(x16, P, so, pe)
+    else:
+        want = once(O.hier_mix_f64(x, P, G, so, pe))
+        want16 = O.hier_mix16("bf16", x16, P, G, so, pe)
+    wx, wv = (once(t) for t in O.hier_sgd_fused_mix_f64(x, v, g, LR, MU, WD, P, G, so, pe))
+    wx16, wv16 = O.hier_sgd_fused_mix16("bf16", x16, v, g16, LR, MU, WD, P, G, so, pe)
+    with tune:
+        for inplace in (False, True):
+            a = dev(x)
+            b = a if inplace else dev(x)
+            cx.cx_hier_mix(a, b, P, G, sod, ped)
+            a16 = d16(x16)
+            b16 = a16 if inplace else d16(x16)
+            cx.cx_hier_mix_bf16(a16, b16, P, G, sod, ped)
+            xi, vi = dev(x), dev(v)
+            xo, vo = (xi, vi) if inplace else (dev(x), dev(v))
+            cx.cx_hier_sgd_fused_mix(xi, xo, vi, vo, dev(g), LR, MU, WD, P, G, sod, ped)
+            yi, ui = d16(x16), dev(v)
+            yo, uo = (yi, ui) if inplace else (d16(x16), dev(v))
+            cx.cx_hier_sgd_fused_mix_bf16(yi, yo, ui, uo, d16(g16), LR, MU, WD, P, G, sod, ped)
+            torch.cuda.synchronize()
+            assert same_bits(host(b), want), inplace
+            assert (h16(b16) == want16).all(), inplace
+            assert same_bits(host(xo), wx) and same_bits(host(vo), wv), inplace
+            assert (h16(yo) == wx16).all() and same_bits(host(uo), wv16), inplace
