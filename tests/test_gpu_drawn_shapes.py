@@ -235,3 +235,53 @@ def test_drawn_shapes_under_drawn_launch_parameters(case):
             assert (h16(b16) == want16).all(), inplace
             assert same_bits(host(xo), wx) and same_bits(host(vo), wv), inplace
             assert (h16(yo) == wx16).all() and same_bits(host(uo), wv16), inplace
+
+
+def test_largest_row_count_in_every_entry_point():
+    """CX_MAX_ROWS gossiping rows -- the longest peer table and the longest cycles the library takes --
+    through the optimizer steps, push-sum and the 16-bit rows, in both buffer modes."""
+    W, P, ld, S = cx.CX_MAX_ROWS, 777, 784, 3
+    so = WL.equal_seg_off(P, S)
+    pe = O.topology(77, W, S, 0, 1)[0]
+    sod, ped = dev(so), dev(pe)
+    x = WL.gen_matrix(W, P, 0.05, seed=77, ld=ld)
+    v = WL.gen_matrix(W, P, 0.02, seed=77, ld=ld, stream=1)
+    g = WL.gen_matrix(W, P, 0.01, seed=77, ld=ld, stream=2)
+    w = (0.5 + np.random.default_rng(77).random(W)).astype(np.float32)
+    x16, g16 = O.f32_to_f16(x), O.f32_to_f16(g)
+    fx, fv = (once(t) for t in O.sgd_fused_mix_f64(x, v, g, LR, MU, WD, P, so, pe))
+    hx, hv = (once(t) for t in O.hier_sgd_fused_mix_f64(x, v, g, LR, MU, WD, P, 1, so, pe))
+    px, pw, pz = O.pushsum_mix_f32(x, w, P, W - 1, True)
+    m16 = O.gossip_mix_f16(x16, P, so, pe)
+    fx16, fv16 = O.sgd_fused_mix16("f16", x16, v, g16, LR, MU, WD, P, so, pe)
+    px16, pw16, pz16 = O.pushsum_mix16("f16", x16, w, P, W - 1, True)
+    assert same_bits(fx, hx) and same_bits(fv, hv)        # groups of one: the flat step
+    for inplace in (False, True):
+        xi, vi = dev(x), dev(v)
+        xo, vo = (xi, vi) if inplace else (dev(x), dev(v))
+        cx.cx_sgd_fused_mix(xi, xo, vi, vo, dev(g), LR, MU, WD, P, sod, ped)
+        yi, ui = dev(x), dev(v)
+        yo, uo = (yi, ui) if inplace else (dev(x), dev(v))
+        cx.cx_hier_sgd_fused_mix(yi, yo, ui, uo, dev(g), LR, MU, WD, P, 1, sod, ped)
+        pi, wi = dev(x), dev(w)
+        po = pi if inplace else dev(x)
+        wo, z = torch.zeros_like(wi), torch.zeros_like(pi)
+        cx.cx_pushsum_mix(pi, po, wi, wo, z, P, W - 1)
+        a16 = d16(x16)
+        b16 = a16 if inplace else d16(x16)
+        cx.cx_gossip_mix_f16(a16, b16, P, sod, ped)
+        c16, cv = d16(x16), dev(v)
+        e16, ev = (c16, cv) if inplace else (d16(x16), dev(v))
+        cx.cx_sgd_fused_mix_f16(c16, e16, cv, ev, d16(g16), LR, MU, WD, P, sod, ped)
+        q16 = d16(x16)
+        r16 = q16 if inplace else d16(x16)
+        wo16, z16 = torch.zeros_like(wi), d16(x16)
+        cx.cx_pushsum_mix_f16(q16, r16, wi, wo16, z16, P, W - 1)
+        torch.cuda.synchronize()
+        assert same_bits(host(xo), fx) and same_bits(host(vo), fv), inplace
+        assert same_bits(host(yo), hx) and same_bits(host(uo), hv), inplace
+        assert same_bits(host(po), px) and same_bits(host(wo), pw) and same_bits(host(z)[:, :P], pz[:, :P]), inplace
+        assert (h16(b16) == m16).all(), inplace
+        assert (h16(e16) == fx16).all() and same_bits(host(ev), fv16), inplace
+        assert (h16(r16) == px16).all() and same_bits(host(wo16), pw16), inplace
+        assert (h16(z16)[:, :P] == pz16[:, :P]).all(), inplace
