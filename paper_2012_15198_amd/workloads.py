@@ -14,7 +14,7 @@ Values are Gaussian with the stated standard deviation.
 from __future__ import annotations
 
 import math
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 from typing import Optional
 
 import numpy as np

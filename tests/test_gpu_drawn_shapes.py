@@ -9,16 +9,12 @@ import torch
 import oracle as O
 from paper_2012_15198_amd import cxmix as cx
 from paper_2012_15198_amd import workloads as WL
-from gpu_util import Tuning, dev, host, same_bits
+from gpu_util import Tuning, dev, host, once, same_bits
 
 pytestmark = pytest.mark.gpu
 
 CASES = 60
 LR, MU, WD = 0.1, 0.9, 1e-4
-
-
-def once(a):
-    return a.astype(np.float32)
 
 
 def d16(a):

@@ -14,7 +14,7 @@ import torch
 import oracle as O
 from paper_2012_15198_amd import cxmix as cx
 from paper_2012_15198_amd import workloads as WL
-from gpu_util import Tuning, bits, dev, host, once, same_bits, within_rel, worst_rel
+from gpu_util import bits, dev, host, once, same_bits, within_rel, worst_rel
 
 pytestmark = pytest.mark.gpu
 REL = 1e-6

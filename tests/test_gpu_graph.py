@@ -12,16 +12,12 @@ import torch
 import oracle as O
 from paper_2012_15198_amd import cxmix as cx
 from paper_2012_15198_amd import workloads as WL
-from gpu_util import dev, host, same_bits
+from gpu_util import dev, host, once, same_bits
 
 pytestmark = pytest.mark.gpu
 
 R = 4                     # even: ping-pong results land in the first buffer again
 LR, MU, WD = 0.1, 0.9, 1e-4
-
-
-def once(a):
-    return a.astype(np.float32)
 
 
 def d16(a):

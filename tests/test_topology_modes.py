@@ -1,7 +1,6 @@
 """CPU tests of the comparison topologies (random without fair selection, one table for all
 segments) in the oracle and the library, and of the mixing-matrix analysis that checks the
 generators against Theorems 1 and 2 of the paper."""
-import math
 from collections import Counter
 
 import numpy as np
