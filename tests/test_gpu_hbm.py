@@ -17,6 +17,8 @@ MiB = 1 << 20
 
 def test_blocks_are_usable_device_memory_and_are_given_back():
     cx.cx_copy_baseline(torch.zeros(1024, device="cuda:0"), torch.zeros(1024, device="cuda:0"))   # runtime and library set up
+    gc.collect()                                       # graphs and streams of earlier tests give their memory back now,
+    torch.cuda.empty_cache()                           # not between the two readings below
     torch.cuda.synchronize()
     free0 = torch.cuda.mem_get_info()[0]
     sizes = [300 * MiB + 12345, 70 * MiB, 1]           # several pieces + a ragged tail; under one piece; one byte
@@ -25,7 +27,8 @@ def test_blocks_are_usable_device_memory_and_are_given_back():
         assert len(set(ptrs)) == 3 and all(p and p % (2 * MiB) == 0 for p in ptrs)
         held = free0 - torch.cuda.mem_get_info()[0]
         rounded = sum((s + 2 * MiB - 1) // (2 * MiB) * (2 * MiB) for s in sizes)
-        assert rounded <= held <= rounded + 256 * MiB     # the fillers are gone again (some slack for page tables)
+        # the fillers are gone again; slack for page tables above, for what the runtime frees lazily below
+        assert rounded - 64 * MiB <= held <= rounded + 256 * MiB
         with pytest.raises(cx.CxError, match="CX_ERR_UNSUPPORTED"):
             cx.cx_hbm_free(ptrs[0] + 2 * MiB)              # inside a block, not its start
     finally:
@@ -80,7 +83,9 @@ def test_mix_on_placed_tensors_matches_the_oracle_and_plain_tensors():
 def test_placement_on_a_nearly_full_device():
     """Most of the memory held by somebody else (torch): the call still serves what fits -- with little or
     nothing left to skip -- says CX_ERR_MEMORY for what does not, and gives everything back."""
+    gc.collect()
     torch.cuda.empty_cache()
+    torch.cuda.synchronize()
     free0 = torch.cuda.mem_get_info()[0]
     keep = 24 << 30
     if free0 < keep + (8 << 30):
